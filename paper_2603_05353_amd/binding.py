@@ -1,0 +1,219 @@
+"""ctypes binding of libifkv.so (include/ifkv.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch is used to allocate device memory and to name the stream.  If
+the library has not been built the import of any entry point fails loudly;
+there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libifkv.so")
+
+IFKV_OK, IFKV_EINVAL, IFKV_ESHAPE, IFKV_EDTYPE, IFKV_ENOMEM, IFKV_EHIP = 0, -1, -2, -3, -4, -5
+IFKV_F32, IFKV_BF16 = 0, 1
+IFKV_ROPE_HALF, IFKV_ROPE_INTERLEAVED = 0, 1
+IFKV_FLAG_FORCE_GENERIC = 1
+
+EXPORTS = (
+    "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
+    "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
+    "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_copy_bytes",
+)
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [
+        ("dtype", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("rope_theta", C.c_double), ("inv_freq", C.POINTER(C.c_double)),
+        ("pairing", C.c_int32), ("sm_scale", C.c_float), ("max_ctx", C.c_int64),
+        ("max_prompt", C.c_int32), ("flags", C.c_uint32),
+    ]
+
+
+class IfkvError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"ifkv error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libifkv.so; raises if it has not been built (no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_05353_amd.build` "
+            "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.ifkv_create.argtypes = [C.POINTER(vp), C.POINTER(LayerDesc), vp]
+    lib.ifkv_create.restype = C.c_int
+    lib.ifkv_destroy.argtypes = [vp]
+    lib.ifkv_destroy.restype = None
+    lib.ifkv_last_error.argtypes = [vp]
+    lib.ifkv_last_error.restype = C.c_char_p
+    lib.ifkv_version.argtypes = []
+    lib.ifkv_version.restype = C.c_char_p
+    lib.ifkv_reposition_keys.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32),
+                                         C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), vp, vp,
+                                         C.POINTER(i64), C.POINTER(i64)]
+    lib.ifkv_reposition_keys.restype = C.c_int
+    lib.ifkv_score_tokens.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp]
+    lib.ifkv_score_tokens.restype = C.c_int
+    lib.ifkv_select_topk.argtypes = [vp, vp, i64, C.c_double, i64, vp, C.POINTER(i64)]
+    lib.ifkv_select_topk.restype = C.c_int
+    lib.ifkv_recompute_attention.argtypes = [vp, vp, vp, i64, vp, vp, i64, vp, vp]
+    lib.ifkv_recompute_attention.restype = C.c_int
+    lib.ifkv_splice_kv.argtypes = [vp, vp, vp, vp, i64, vp, vp, i64]
+    lib.ifkv_splice_kv.restype = C.c_int
+    lib.ifkv_copy_bytes.argtypes = [vp, vp, vp, i64]
+    lib.ifkv_copy_bytes.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _i32_array(x: Optional[Sequence[int]]):
+    if x is None:
+        return None
+    return (C.c_int32 * len(x))(*[int(v) for v in x])
+
+
+def _i64_array(x: Optional[Sequence[int]]):
+    if x is None:
+        return None
+    return (C.c_int64 * len(x))(*[int(v) for v in x])
+
+
+_TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+_ENUM_DTYPE = {"f32": IFKV_F32, "bf16": IFKV_BF16}
+
+
+class Layer:
+    """One ifkv_ctx: a layer shape bound to a HIP stream."""
+
+    def __init__(self, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float,
+                 max_ctx: int, max_prompt: int, pairing: str = "half", sm_scale: float = 0.0,
+                 inv_freq: Optional[Sequence[float]] = None, flags: int = 0,
+                 stream: Optional[int] = None, device: str = "cuda:0"):
+        self._lib = load_library()
+        self.dtype = dtype
+        self.torch_dtype = _TORCH_DTYPE[dtype]
+        self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
+        self.device = device
+        desc = LayerDesc()
+        desc.dtype = _ENUM_DTYPE[dtype]
+        desc.n_q_heads, desc.n_kv_heads, desc.head_dim = n_q_heads, n_kv_heads, head_dim
+        desc.rope_theta = float(rope_theta)
+        self._freq = None
+        if inv_freq is not None:
+            self._freq = (C.c_double * len(inv_freq))(*[float(v) for v in inv_freq])
+            desc.inv_freq = C.cast(self._freq, C.POINTER(C.c_double))
+        desc.pairing = IFKV_ROPE_HALF if pairing == "half" else IFKV_ROPE_INTERLEAVED
+        desc.sm_scale = float(sm_scale)
+        desc.max_ctx, desc.max_prompt, desc.flags = int(max_ctx), int(max_prompt), int(flags)
+        if stream is None and torch.cuda.is_available():
+            stream = torch.cuda.current_stream().cuda_stream
+        self._ctx = C.c_void_p()
+        rc = self._lib.ifkv_create(C.byref(self._ctx), C.byref(desc), C.c_void_p(stream or 0))
+        if rc != IFKV_OK:
+            raise IfkvError(rc, self._lib.ifkv_last_error(None).decode())
+
+    # -- plumbing -----------------------------------------------------------
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._lib.ifkv_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != IFKV_OK:
+            raise IfkvError(rc, self._lib.ifkv_last_error(self._ctx).decode())
+
+    def _empty(self, *shape, dtype=None):
+        return torch.empty(*shape, dtype=dtype or self.torch_dtype, device=self.device)
+
+    # -- the five stages ------------------------------------------------------
+    def reposition_keys(self, k_chunks: List[torch.Tensor], v_chunks: Optional[List[torch.Tensor]] = None,
+                        chunk_order: Optional[Sequence[int]] = None,
+                        cached_pos0: Optional[Sequence[int]] = None,
+                        delta_override: Optional[Sequence[int]] = None,
+                        k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None
+                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor], List[int], int]:
+        n = len(k_chunks)
+        lens = [int(t.shape[0]) for t in k_chunks]
+        N = sum(lens)
+        if k_out is None:
+            k_out = self._empty(N, self.n_kv_heads, self.head_dim)
+        if v_chunks is not None and v_out is None:
+            v_out = self._empty(N, self.n_kv_heads, self.head_dim)
+        kp = (C.c_void_p * n)(*[t.data_ptr() if t.shape[0] else None for t in k_chunks])
+        vp = None
+        if v_chunks is not None:
+            vp = (C.c_void_p * n)(*[t.data_ptr() if t.shape[0] else None for t in v_chunks])
+        starts = (C.c_int64 * max(n, 1))()
+        n_ctx = C.c_int64()
+        self._check(self._lib.ifkv_reposition_keys(
+            self._ctx, n, kp, vp, _i32_array(lens), _i32_array(chunk_order), _i32_array(cached_pos0),
+            _i64_array(delta_override), _ptr(k_out), _ptr(v_out), starts, C.byref(n_ctx)))
+        return k_out, v_out, [int(starts[i]) for i in range(n)], int(n_ctx.value)
+
+    def score_tokens(self, k_global: torch.Tensor, q_prompt: torch.Tensor,
+                     k_prompt: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                     accumulate: bool = False) -> torch.Tensor:
+        n_ctx, m = int(k_global.shape[0]), int(q_prompt.shape[0])
+        if scores is None:
+            scores = self._empty(n_ctx, dtype=torch.float32)
+        self._check(self._lib.ifkv_score_tokens(self._ctx, _ptr(k_global), n_ctx, _ptr(q_prompt), m,
+                                                _ptr(k_prompt), int(accumulate), _ptr(scores)))
+        return scores
+
+    def select_topk(self, scores: torch.Tensor, ratio: float = 0.0, k: int = -1,
+                    idx_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n_ctx = int(scores.shape[0])
+        if idx_out is None:
+            want = k if k >= 0 else int(math.floor(float(ratio) * n_ctx)) if 0.0 <= ratio <= 1.0 else 0
+            idx_out = self._empty(max(want, 1), dtype=torch.int32)
+        k_out = C.c_int64()
+        self._check(self._lib.ifkv_select_topk(self._ctx, _ptr(scores), n_ctx, float(ratio), int(k),
+                                               _ptr(idx_out), C.byref(k_out)))
+        return idx_out[: int(k_out.value)]
+
+    def recompute_attention(self, q_sel: torch.Tensor, row_pos: torch.Tensor, k_cache: torch.Tensor,
+                            v_cache: torch.Tensor, out: Optional[torch.Tensor] = None,
+                            return_lse: bool = False):
+        n_rows, n_kv = int(q_sel.shape[0]), int(k_cache.shape[0])
+        if out is None:
+            out = self._empty(n_rows, self.n_q_heads, self.head_dim)
+        lse = self._empty(n_rows, self.n_q_heads, dtype=torch.float32) if return_lse else None
+        self._check(self._lib.ifkv_recompute_attention(self._ctx, _ptr(q_sel), _ptr(row_pos), n_rows,
+                                                       _ptr(k_cache), _ptr(v_cache), n_kv, _ptr(out), _ptr(lse)))
+        return (out, lse) if return_lse else out
+
+    def splice_kv(self, k_new: torch.Tensor, v_new: Optional[torch.Tensor], idx: torch.Tensor,
+                  k_cache: torch.Tensor, v_cache: Optional[torch.Tensor]) -> None:
+        self._check(self._lib.ifkv_splice_kv(self._ctx, _ptr(k_new), _ptr(v_new), _ptr(idx), int(idx.shape[0]),
+                                             _ptr(k_cache), _ptr(v_cache), int(k_cache.shape[0])))
+
+    def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor) -> None:
+        self._check(self._lib.ifkv_copy_bytes(self._ctx, _ptr(dst), _ptr(src), src.numel() * src.element_size()))

@@ -1,0 +1,13 @@
+// Declarations shared by the two attention translation units.
+#pragma once
+
+#include "ifkv_internal.h"
+
+namespace ifkv {
+
+bool attention_mfma_supported(const ifkv_ctx *ctx);
+hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
+                                 const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
+                                 float *lse_out);
+
+}  // namespace ifkv

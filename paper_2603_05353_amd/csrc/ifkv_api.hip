@@ -1,0 +1,304 @@
+// Host side of the C ABI declared in include/ifkv.h: argument validation
+// (before any GPU call), host-side bookkeeping (chunk starts, budget), scratch
+// management and dispatch to the stage launchers.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ifkv_internal.h"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+int fail(ifkv_ctx *ctx, int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  if (ctx != nullptr)
+    ctx->err = buf;
+  else
+    g_create_error = buf;
+  return code;
+}
+
+int hip_fail(ifkv_ctx *ctx, hipError_t e, const char *what) {
+  return fail(ctx, IFKV_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Grows the context's scratch buffer to at least `bytes`.
+int ensure_scratch(ifkv_ctx *ctx, size_t bytes) {
+  if (bytes <= ctx->scratch_bytes) return IFKV_OK;
+  if (ctx->scratch != nullptr) {
+    hipError_t e = hipStreamSynchronize(ctx->stream);  // earlier kernels may still use the old buffer
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipStreamSynchronize");
+    (void)hipFree(ctx->scratch);
+    ctx->scratch = nullptr;
+    ctx->scratch_bytes = 0;
+  }
+  void *p = nullptr;
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, IFKV_ENOMEM, "scratch allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+  }
+  ctx->scratch = p;
+  ctx->scratch_bytes = bytes;
+  return IFKV_OK;
+}
+
+int ensure_inv_freq(ifkv_ctx *ctx) {
+  if (ctx->d_inv_freq != nullptr) return IFKV_OK;
+  const size_t bytes = sizeof(double) * (ctx->desc.head_dim / 2);
+  void *p = nullptr;
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, IFKV_ENOMEM, "frequency table allocation failed: %s", hipGetErrorString(e));
+  }
+  e = hipMemcpy(p, ctx->inv_freq, bytes, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(p);
+    return hip_fail(ctx, e, "hipMemcpy(inv_freq)");
+  }
+  ctx->d_inv_freq = static_cast<double *>(p);
+  return IFKV_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *ifkv_version(void) { return "0.1"; }
+
+const char *ifkv_last_error(const ifkv_ctx *ctx) {
+  return ctx != nullptr ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+int ifkv_create(ifkv_ctx **out, const ifkv_layer_desc *desc, void *hip_stream) {
+  if (out == nullptr) return fail(nullptr, IFKV_EINVAL, "ifkv_create: out is NULL");
+  *out = nullptr;
+  if (desc == nullptr) return fail(nullptr, IFKV_EINVAL, "ifkv_create: desc is NULL");
+  if (desc->dtype != IFKV_F32 && desc->dtype != IFKV_BF16)
+    return fail(nullptr, IFKV_EDTYPE, "ifkv_create: unknown dtype %d", desc->dtype);
+  if (desc->pairing != IFKV_ROPE_HALF && desc->pairing != IFKV_ROPE_INTERLEAVED)
+    return fail(nullptr, IFKV_EDTYPE, "ifkv_create: unknown rope pairing %d", desc->pairing);
+  if (desc->n_q_heads <= 0 || desc->n_kv_heads <= 0 || desc->n_q_heads % desc->n_kv_heads != 0)
+    return fail(nullptr, IFKV_EINVAL, "ifkv_create: n_q_heads=%d must be a positive multiple of n_kv_heads=%d",
+                desc->n_q_heads, desc->n_kv_heads);
+  if (desc->head_dim != 64 && desc->head_dim != 128)
+    return fail(nullptr, IFKV_EINVAL, "ifkv_create: head_dim=%d is not supported (64 or 128)", desc->head_dim);
+  if (desc->inv_freq == nullptr && !(desc->rope_theta > 0.0))
+    return fail(nullptr, IFKV_EINVAL, "ifkv_create: rope_theta must be positive");
+  if (!(desc->sm_scale >= 0.f) || !std::isfinite(desc->sm_scale))
+    return fail(nullptr, IFKV_EINVAL, "ifkv_create: sm_scale must be finite and >= 0");
+  if (desc->max_ctx <= 0 || desc->max_ctx >= (int64_t(1) << 31))
+    return fail(nullptr, IFKV_EINVAL, "ifkv_create: max_ctx must be in [1, 2^31)");
+  if (desc->max_prompt < 0) return fail(nullptr, IFKV_EINVAL, "ifkv_create: max_prompt must be >= 0");
+
+  ifkv_ctx *ctx = new (std::nothrow) ifkv_ctx();
+  if (ctx == nullptr) return fail(nullptr, IFKV_ENOMEM, "ifkv_create: out of host memory");
+  ctx->desc = *desc;
+  ctx->desc.inv_freq = nullptr;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  ctx->sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / std::sqrt(static_cast<float>(desc->head_dim));
+  const int half = desc->head_dim / 2;
+  for (int j = 0; j < half; ++j) {
+    ctx->inv_freq[j] = desc->inv_freq != nullptr
+                           ? desc->inv_freq[j]
+                           : std::pow(desc->rope_theta, -2.0 * static_cast<double>(j) / desc->head_dim);
+  }
+  *out = ctx;
+  return IFKV_OK;
+}
+
+void ifkv_destroy(ifkv_ctx *ctx) {
+  if (ctx == nullptr) return;
+  if (ctx->scratch != nullptr) (void)hipFree(ctx->scratch);
+  if (ctx->d_inv_freq != nullptr) (void)hipFree(ctx->d_inv_freq);
+  delete ctx;
+}
+
+int ifkv_reposition_keys(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_chunks,
+                         const void *const *v_chunks, const int32_t *chunk_len,
+                         const int32_t *chunk_order, const int32_t *cached_pos0,
+                         const int64_t *delta_override, void *k_out, void *v_out,
+                         int64_t *chunk_start_out, int64_t *n_ctx_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_chunks < 0) return fail(ctx, IFKV_EINVAL, "reposition_keys: n_chunks=%d is negative", n_chunks);
+  if (n_chunks > 0 && (k_chunks == nullptr || chunk_len == nullptr))
+    return fail(ctx, IFKV_EINVAL, "reposition_keys: k_chunks and chunk_len are required");
+
+  // Eq. (5): start of every chunk in the concatenation order
+  std::vector<int64_t> start(n_chunks, 0);
+  std::vector<char> seen(n_chunks, 0);
+  int64_t n_ctx = 0;
+  for (int s = 0; s < n_chunks; ++s) {
+    const int c = chunk_order != nullptr ? chunk_order[s] : s;
+    if (c < 0 || c >= n_chunks || seen[c])
+      return fail(ctx, IFKV_EINVAL, "reposition_keys: chunk_order is not a permutation (slot %d -> %d)", s, c);
+    seen[c] = 1;
+    if (chunk_len[c] < 0) return fail(ctx, IFKV_EINVAL, "reposition_keys: chunk_len[%d] is negative", c);
+    start[c] = n_ctx;
+    n_ctx += chunk_len[c];
+  }
+  if (n_ctx > ctx->desc.max_ctx)
+    return fail(ctx, IFKV_ESHAPE, "reposition_keys: %lld context rows exceed max_ctx=%lld",
+                static_cast<long long>(n_ctx), static_cast<long long>(ctx->desc.max_ctx));
+  for (int c = 0; c < n_chunks; ++c) {
+    if (chunk_len[c] > 0) {
+      if (k_chunks[c] == nullptr) return fail(ctx, IFKV_EINVAL, "reposition_keys: k_chunks[%d] is NULL", c);
+      if (v_chunks != nullptr && v_chunks[c] == nullptr)
+        return fail(ctx, IFKV_EINVAL, "reposition_keys: v_chunks[%d] is NULL", c);
+      if (!aligned16(k_chunks[c]) || (v_chunks != nullptr && !aligned16(v_chunks[c])))
+        return fail(ctx, IFKV_EINVAL, "reposition_keys: chunk %d is not 16-byte aligned", c);
+    }
+  }
+  if (n_ctx > 0) {
+    if (k_out == nullptr) return fail(ctx, IFKV_EINVAL, "reposition_keys: k_out is NULL");
+    if (v_chunks != nullptr && v_out == nullptr) return fail(ctx, IFKV_EINVAL, "reposition_keys: v_out is NULL");
+    if (!aligned16(k_out) || (v_chunks != nullptr && !aligned16(v_out)))
+      return fail(ctx, IFKV_EINVAL, "reposition_keys: outputs must be 16-byte aligned");
+  }
+  if (chunk_start_out != nullptr)
+    for (int c = 0; c < n_chunks; ++c) chunk_start_out[c] = start[c];
+  if (n_ctx_out != nullptr) *n_ctx_out = n_ctx;
+  if (n_ctx == 0) return IFKV_OK;
+
+  int rc = ensure_inv_freq(ctx);
+  if (rc != IFKV_OK) return rc;
+
+  const int rows_per_tile = ifkv::reposition_rows_per_tile();
+  ifkv::RepoBatch batch;
+  batch.n = 0;
+  batch.total_tiles = 0;
+  auto flush = [&]() -> int {
+    if (batch.n == 0) return IFKV_OK;
+    hipError_t e = ifkv::launch_reposition(ctx, batch, k_out, v_chunks != nullptr ? v_out : nullptr);
+    batch.n = 0;
+    batch.total_tiles = 0;
+    return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "reposition kernel launch");
+  };
+  for (int c = 0; c < n_chunks; ++c) {
+    if (chunk_len[c] == 0) continue;
+    ifkv::RepoChunk &rc_ = batch.c[batch.n];
+    rc_.k = k_chunks[c];
+    rc_.v = v_chunks != nullptr ? v_chunks[c] : nullptr;
+    rc_.dst_row = start[c];
+    const int64_t adv = delta_override != nullptr
+                            ? delta_override[c]
+                            : start[c] - (cached_pos0 != nullptr ? static_cast<int64_t>(cached_pos0[c]) : 0);
+    rc_.advance = static_cast<double>(adv);
+    rc_.len = chunk_len[c];
+    rc_.tile0 = batch.total_tiles;
+    batch.total_tiles += (chunk_len[c] + rows_per_tile - 1) / rows_per_tile;
+    if (++batch.n == ifkv::kRepoMaxChunks) {
+      rc = flush();
+      if (rc != IFKV_OK) return rc;
+    }
+  }
+  return flush();
+}
+
+int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
+                      int32_t m_prompt, const void *k_prompt, int32_t accumulate, float *scores) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_ctx < 0 || m_prompt < 0) return fail(ctx, IFKV_EINVAL, "score_tokens: negative size");
+  if (n_ctx > ctx->desc.max_ctx)
+    return fail(ctx, IFKV_ESHAPE, "score_tokens: n_ctx=%lld exceeds max_ctx=%lld", static_cast<long long>(n_ctx),
+                static_cast<long long>(ctx->desc.max_ctx));
+  if (m_prompt > ctx->desc.max_prompt)
+    return fail(ctx, IFKV_ESHAPE, "score_tokens: m_prompt=%d exceeds max_prompt=%d", m_prompt, ctx->desc.max_prompt);
+  if (n_ctx == 0) return IFKV_OK;
+  if (scores == nullptr) return fail(ctx, IFKV_EINVAL, "score_tokens: scores is NULL");
+  if (m_prompt > 0 && (k_global == nullptr || q_prompt == nullptr))
+    return fail(ctx, IFKV_EINVAL, "score_tokens: k_global and q_prompt are required");
+  if (!aligned16(k_global) || !aligned16(q_prompt) || !aligned16(k_prompt))
+    return fail(ctx, IFKV_EINVAL, "score_tokens: inputs must be 16-byte aligned");
+  int rc = ensure_scratch(ctx, ifkv::score_scratch_bytes(ctx, n_ctx, m_prompt));
+  if (rc != IFKV_OK) return rc;
+  hipError_t e = ifkv::launch_score(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate != 0, scores);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "score kernel launch");
+}
+
+int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double ratio, int64_t k_override,
+                     int32_t *idx_out, int64_t *k_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_ctx < 0) return fail(ctx, IFKV_EINVAL, "select_topk: n_ctx is negative");
+  if (n_ctx > ctx->desc.max_ctx || n_ctx >= (int64_t(1) << 31))
+    return fail(ctx, IFKV_ESHAPE, "select_topk: n_ctx=%lld exceeds max_ctx", static_cast<long long>(n_ctx));
+  int64_t k;
+  if (k_override >= 0) {
+    k = k_override;
+  } else {
+    if (!(ratio >= 0.0 && ratio <= 1.0))
+      return fail(ctx, IFKV_EINVAL, "select_topk: ratio=%g is outside [0, 1]", ratio);
+    k = static_cast<int64_t>(std::floor(ratio * static_cast<double>(n_ctx)));  // k = floor(rho N)
+  }
+  if (k > n_ctx)
+    return fail(ctx, IFKV_EINVAL, "select_topk: k=%lld exceeds n_ctx=%lld", static_cast<long long>(k),
+                static_cast<long long>(n_ctx));
+  if (k_out != nullptr) *k_out = k;
+  if (k == 0) return IFKV_OK;
+  if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk: NULL pointer");
+  hipError_t e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "top-k kernel launch");
+}
+
+int ifkv_recompute_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
+                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
+                             float *lse_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_rows < 0 || n_kv < 0) return fail(ctx, IFKV_EINVAL, "recompute_attention: negative size");
+  if (n_kv > ctx->desc.max_ctx)
+    return fail(ctx, IFKV_ESHAPE, "recompute_attention: n_kv=%lld exceeds max_ctx=%lld",
+                static_cast<long long>(n_kv), static_cast<long long>(ctx->desc.max_ctx));
+  if (n_rows >= (int64_t(1) << 31)) return fail(ctx, IFKV_ESHAPE, "recompute_attention: too many rows");
+  if (n_rows == 0) return IFKV_OK;
+  if (n_kv == 0) return fail(ctx, IFKV_EINVAL, "recompute_attention: rows given but the cache is empty");
+  if (q_sel == nullptr || row_pos == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr)
+    return fail(ctx, IFKV_EINVAL, "recompute_attention: NULL pointer");
+  if (!aligned16(q_sel) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
+    return fail(ctx, IFKV_EINVAL, "recompute_attention: tensors must be 16-byte aligned");
+  int rc = ensure_scratch(ctx, ifkv::attention_scratch_bytes(ctx, n_rows, n_kv));
+  if (rc != IFKV_OK) return rc;
+  hipError_t e = ifkv::launch_attention(ctx, q_sel, row_pos, n_rows, k_cache, v_cache, n_kv, out, lse_out);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "attention kernel launch");
+}
+
+int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new, const int32_t *idx, int64_t n_rows,
+                   void *k_cache, void *v_cache, int64_t n_kv) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_rows < 0 || n_kv < 0) return fail(ctx, IFKV_EINVAL, "splice_kv: negative size");
+  if (n_kv > ctx->desc.max_ctx)
+    return fail(ctx, IFKV_ESHAPE, "splice_kv: n_kv=%lld exceeds max_ctx=%lld", static_cast<long long>(n_kv),
+                static_cast<long long>(ctx->desc.max_ctx));
+  if (n_rows == 0) return IFKV_OK;
+  if (k_new == nullptr || idx == nullptr || k_cache == nullptr)
+    return fail(ctx, IFKV_EINVAL, "splice_kv: NULL pointer");
+  if ((v_new == nullptr) != (v_cache == nullptr))
+    return fail(ctx, IFKV_EINVAL, "splice_kv: v_new and v_cache must both be given or both be NULL");
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+    return fail(ctx, IFKV_EINVAL, "splice_kv: tensors must be 16-byte aligned");
+  hipError_t e = ifkv::launch_splice(ctx, k_new, v_new, idx, n_rows, k_cache, v_cache, n_kv);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "splice kernel launch");
+}
+
+int ifkv_copy_bytes(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_bytes < 0 || (n_bytes & 15) != 0) return fail(ctx, IFKV_EINVAL, "copy_bytes: size must be a multiple of 16");
+  if (n_bytes == 0) return IFKV_OK;
+  if (dst == nullptr || src == nullptr || !aligned16(dst) || !aligned16(src))
+    return fail(ctx, IFKV_EINVAL, "copy_bytes: pointers must be non-NULL and 16-byte aligned");
+  hipError_t e = ifkv::launch_copy(ctx, dst, src, n_bytes);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "copy kernel launch");
+}
+
+}  // extern "C"

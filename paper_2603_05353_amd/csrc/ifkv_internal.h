@@ -1,0 +1,72 @@
+// Internal declarations shared by the host-side C ABI and the per-stage HIP
+// translation units.  Not installed; the public interface is include/ifkv.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "ifkv.h"
+
+struct ifkv_ctx {
+  ifkv_layer_desc desc;
+  hipStream_t stream = nullptr;
+  float sm_scale = 0.f;
+  double inv_freq[128];         // d/2 entries, host copy
+  double *d_inv_freq = nullptr; // device copy, uploaded on first use
+  void *scratch = nullptr;      // device scratch, grown on demand
+  size_t scratch_bytes = 0;
+  std::string err;
+};
+
+namespace ifkv {
+
+constexpr int kMaxHeadDim = 256;
+
+inline size_t dtype_size(int dtype) { return dtype == IFKV_BF16 ? 2 : 4; }
+
+// ---- stage launchers (each returns a hipError_t from launch checking) ------
+
+// Stage 1.  One launch handles up to kRepoMaxChunks chunks; descriptors travel
+// by value in the kernel arguments so no staging copy or host sync is needed.
+constexpr int kRepoMaxChunks = 64;
+struct RepoChunk {
+  const void *k;    // device, [len, H_kv, d]
+  const void *v;    // device or null
+  int64_t dst_row;  // first row in the concatenated cache
+  double advance;   // rotary phase advance in positions
+  int32_t len;
+  int32_t tile0;    // first tile index of this chunk within the launch
+};
+struct RepoBatch {
+  RepoChunk c[kRepoMaxChunks];
+  int32_t n;
+  int32_t total_tiles;
+};
+hipError_t launch_reposition(ifkv_ctx *ctx, const RepoBatch &batch, void *k_out, void *v_out);
+int reposition_rows_per_tile();
+
+// Stage 2.
+size_t score_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt);
+hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
+                        int m_prompt, const void *k_prompt, int accumulate, float *scores);
+
+// Stage 3.
+size_t topk_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx);
+hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out);
+
+// Stage 4.
+size_t attention_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv);
+hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
+                            const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
+                            float *lse_out);
+
+// Stage 5.
+hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, const int32_t *idx,
+                         int64_t n_rows, void *k_cache, void *v_cache, int64_t n_kv);
+
+// Calibration copy.
+hipError_t launch_copy(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes);
+
+}  // namespace ifkv

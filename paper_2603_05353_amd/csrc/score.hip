@@ -1,0 +1,237 @@
+// Stage 2 -- Eq. (7): s_j = sum_i A_ij, the attention mass each context token
+// receives from the prompt, averaged over query heads.
+//
+// A (M x N per head) is never stored.  The softmax normaliser of every prompt
+// row is global over the context, so the stage is two sweeps over the keys:
+//   pass A: per (head, prompt row) running max m and sum Z = sum_j exp(l - m),
+//           computed per slice of the context and merged;
+//   pass B: s_j = (1/H_q) sum_h sum_i exp(l_hij - m_hi) / Z_hi.
+// All arithmetic on logits, exponentials and sums is fp32.
+//
+// This file holds the plain fp32 ALU kernels (any dtype; used for fp32 layers
+// and for cross-checking).  The bf16 MFMA kernels live in score_mfma.hip.
+#include "ifkv_device.h"
+#include "ifkv_internal.h"
+#include "score_common.h"
+
+namespace ifkv {
+
+namespace {
+
+constexpr int kStatThreads = 128;  // one prompt row per thread
+constexpr int kStatTile = 32;      // context tokens staged in LDS per step
+
+// Pass A: partial (m, Z) of one slice of the context for 128 prompt rows of one head.
+template <typename Tag, int D>
+__global__ __launch_bounds__(kStatThreads) void score_stats_generic(const void *__restrict__ k_global, int64_t n_ctx,
+                                                                    const void *__restrict__ q_prompt, int m_prompt,
+                                                                    int n_q_heads, int n_kv_heads, float sm_scale,
+                                                                    int slice_len, float2 *__restrict__ partial) {
+  using E = Elem<Tag>;
+  __shared__ float ks[kStatTile][D];
+  const int slice = blockIdx.x;
+  const int h = blockIdx.y;
+  const int r = blockIdx.z * kStatThreads + threadIdx.x;
+  const int g = h / (n_q_heads / n_kv_heads);
+  const bool active = r < m_prompt;
+
+  float q[D];
+  if (active) {
+    const int64_t qoff = (static_cast<int64_t>(r) * n_q_heads + h) * D;
+#pragma unroll
+    for (int c = 0; c < D; ++c) q[c] = E::load1(q_prompt, qoff + c) * sm_scale;
+  } else {
+#pragma unroll
+    for (int c = 0; c < D; ++c) q[c] = 0.f;
+  }
+
+  const int64_t j_begin = static_cast<int64_t>(slice) * slice_len;
+  const int64_t j_end = min(n_ctx, j_begin + slice_len);
+  float m = -INFINITY, z = 0.f;
+  for (int64_t j0 = j_begin; j0 < j_end; j0 += kStatTile) {
+    const int nt = static_cast<int>(min<int64_t>(kStatTile, j_end - j0));
+    __syncthreads();
+    for (int e = threadIdx.x; e < nt * D; e += kStatThreads) {
+      const int jj = e / D, c = e - jj * D;
+      ks[jj][c] = E::load1(k_global, ((j0 + jj) * n_kv_heads + g) * D + c);
+    }
+    __syncthreads();
+    for (int jj = 0; jj < nt; ++jj) {
+      float dot = 0.f;
+#pragma unroll
+      for (int c = 0; c < D; ++c) dot = fmaf(q[c], ks[jj][c], dot);
+      const float mn = fmaxf(m, dot);
+      z = z * expf(m - mn) + expf(dot - mn);
+      m = mn;
+    }
+  }
+  if (active) partial[(static_cast<int64_t>(slice) * n_q_heads + h) * m_prompt + r] = make_float2(m, z);
+}
+
+// Merge the per-slice partials of each (head, row); optionally extend the
+// normaliser over the prompt keys the row sees causally (rows 0..r).  Writes
+// (m, 1/Z).
+template <typename Tag, int D>
+__global__ __launch_bounds__(128) void score_merge_kernel(const float2 *__restrict__ partial, int n_slices,
+                                                          const void *__restrict__ q_prompt,
+                                                          const void *__restrict__ k_prompt, int m_prompt,
+                                                          int n_q_heads, int n_kv_heads, float sm_scale,
+                                                          float2 *__restrict__ stats) {
+  using E = Elem<Tag>;
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_q_heads * m_prompt) return;
+  const int h = t / m_prompt, r = t - h * m_prompt;
+  float m = -INFINITY, z = 0.f;
+  for (int s = 0; s < n_slices; ++s) {
+    const float2 p = partial[(static_cast<int64_t>(s) * n_q_heads + h) * m_prompt + r];
+    if (p.y > 0.f) {
+      const float mn = fmaxf(m, p.x);
+      z = z * expf(m - mn) + p.y * expf(p.x - mn);
+      m = mn;
+    }
+  }
+  if (k_prompt != nullptr) {
+    const int g = h / (n_q_heads / n_kv_heads);
+    const int64_t qoff = (static_cast<int64_t>(r) * n_q_heads + h) * D;
+    for (int tt = 0; tt <= r; ++tt) {
+      const int64_t koff = (static_cast<int64_t>(tt) * n_kv_heads + g) * D;
+      float dot = 0.f;
+      for (int c = 0; c < D; ++c) dot = fmaf(E::load1(q_prompt, qoff + c) * sm_scale, E::load1(k_prompt, koff + c), dot);
+      const float mn = fmaxf(m, dot);
+      z = z * expf(m - mn) + expf(dot - mn);
+      m = mn;
+    }
+  }
+  stats[h * m_prompt + r] = make_float2(m, z > 0.f ? 1.f / z : 0.f);
+}
+
+constexpr int kColThreads = 256;  // one context token per thread
+constexpr int kColRows = 32;      // prompt rows staged in LDS per step
+
+// Pass B: column sums with the final (m, 1/Z).
+template <typename Tag, int D>
+__global__ __launch_bounds__(kColThreads) void score_colsum_generic(const void *__restrict__ k_global, int64_t n_ctx,
+                                                                    const void *__restrict__ q_prompt, int m_prompt,
+                                                                    int n_q_heads, int n_kv_heads, float sm_scale,
+                                                                    const float2 *__restrict__ stats, int accumulate,
+                                                                    float *__restrict__ scores) {
+  using E = Elem<Tag>;
+  __shared__ float qs[kColRows][D];
+  __shared__ float2 st[kColRows];
+  const int64_t j = static_cast<int64_t>(blockIdx.x) * kColThreads + threadIdx.x;
+  const bool active = j < n_ctx;
+  const int G = n_q_heads / n_kv_heads;
+  float acc = 0.f;
+  for (int g = 0; g < n_kv_heads; ++g) {
+    float kreg[D];
+    if (active) {
+      const int64_t koff = (j * n_kv_heads + g) * D;
+#pragma unroll
+      for (int c = 0; c < D; ++c) kreg[c] = E::load1(k_global, koff + c);
+    } else {
+#pragma unroll
+      for (int c = 0; c < D; ++c) kreg[c] = 0.f;
+    }
+    for (int hh = 0; hh < G; ++hh) {
+      const int h = g * G + hh;
+      for (int r0 = 0; r0 < m_prompt; r0 += kColRows) {
+        const int nr = min(kColRows, m_prompt - r0);
+        __syncthreads();
+        for (int e = threadIdx.x; e < nr * D; e += kColThreads) {
+          const int rr = e / D, c = e - rr * D;
+          qs[rr][c] = E::load1(q_prompt, (static_cast<int64_t>(r0 + rr) * n_q_heads + h) * D + c) * sm_scale;
+        }
+        if (threadIdx.x < nr) st[threadIdx.x] = stats[h * m_prompt + r0 + threadIdx.x];
+        __syncthreads();
+        for (int rr = 0; rr < nr; ++rr) {
+          float dot = 0.f;
+#pragma unroll
+          for (int c = 0; c < D; ++c) dot = fmaf(qs[rr][c], kreg[c], dot);
+          acc += expf(dot - st[rr].x) * st[rr].y;
+        }
+      }
+    }
+  }
+  if (active) {
+    const float v = acc / static_cast<float>(n_q_heads);
+    scores[j] = accumulate ? scores[j] + v : v;
+  }
+}
+
+__global__ void fill_zero_kernel(float *p, int64_t n) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+int slice_len_for(int64_t n_ctx) {
+  // at most 64 slices, each a multiple of the LDS tile
+  int64_t sl = (n_ctx + 63) / 64;
+  sl = ((sl + kStatTile - 1) / kStatTile) * kStatTile;
+  if (sl < 128) sl = 128;
+  return static_cast<int>(sl);
+}
+
+template <typename Tag, int D>
+hipError_t run_generic(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt, int m_prompt,
+                       const void *k_prompt, int accumulate, float *scores) {
+  const auto &d = ctx->desc;
+  const int sl = slice_len_for(n_ctx);
+  const int n_slices = static_cast<int>((n_ctx + sl - 1) / sl);
+  ScoreScratch sc = score_scratch_layout(ctx, n_ctx, m_prompt);
+  float2 *partial = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.partial_off);
+  float2 *stats = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.stats_off);
+  hipStream_t st = ctx->stream;
+  dim3 ga(n_slices, d.n_q_heads, (m_prompt + kStatThreads - 1) / kStatThreads);
+  hipLaunchKernelGGL((score_stats_generic<Tag, D>), ga, dim3(kStatThreads), 0, st, k_global, n_ctx, q_prompt,
+                     m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, sl, partial);
+  const int rows = d.n_q_heads * m_prompt;
+  hipLaunchKernelGGL((score_merge_kernel<Tag, D>), dim3((rows + 127) / 128), dim3(128), 0, st, partial, n_slices,
+                     q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
+  hipLaunchKernelGGL((score_colsum_generic<Tag, D>), dim3(static_cast<unsigned>((n_ctx + kColThreads - 1) / kColThreads)),
+                     dim3(kColThreads), 0, st, k_global, n_ctx, q_prompt, m_prompt, d.n_q_heads, d.n_kv_heads,
+                     ctx->sm_scale, stats, accumulate, scores);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt) {
+  const auto &d = ctx->desc;
+  ScoreScratch s;
+  const int64_t rows = static_cast<int64_t>(d.n_q_heads) * (m_prompt > 0 ? m_prompt : 1);
+  const int64_t max_slices = 256;  // upper bound for both the ALU and the MFMA partition
+  s.stats_off = 0;
+  s.partial_off = ((rows * sizeof(float2) + 255) / 256) * 256;
+  s.colpart_off = s.partial_off + ((max_slices * rows * sizeof(float2) + 255) / 256) * 256;
+  // per-(kv head, query chunk) partial column sums of the MFMA pass B
+  const int64_t parts = static_cast<int64_t>(d.n_kv_heads) * kMaxQChunks;
+  s.total = s.colpart_off + static_cast<size_t>(parts) * static_cast<size_t>(n_ctx > 0 ? n_ctx : 1) * sizeof(float);
+  return s;
+}
+
+size_t score_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt) {
+  return score_scratch_layout(ctx, n_ctx, m_prompt).total;
+}
+
+hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt, int m_prompt,
+                        const void *k_prompt, int accumulate, float *scores) {
+  if (n_ctx <= 0) return hipSuccess;
+  const auto &d = ctx->desc;
+  if (m_prompt <= 0) {
+    if (!accumulate)
+      hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<unsigned>((n_ctx + 255) / 256)), dim3(256), 0, ctx->stream,
+                         scores, n_ctx);
+    return hipGetLastError();
+  }
+  const bool generic = (d.flags & IFKV_FLAG_FORCE_GENERIC) || d.dtype != IFKV_BF16 || d.head_dim != 128 ||
+                       !score_mfma_supported(ctx, m_prompt);
+  if (!generic) return launch_score_mfma(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
+  if (d.dtype == IFKV_BF16) {
+    if (d.head_dim == 128) return run_generic<BF16Tag, 128>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
+    return run_generic<BF16Tag, 64>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
+  }
+  if (d.head_dim == 128) return run_generic<F32Tag, 128>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
+  return run_generic<F32Tag, 64>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
+}
+
+}  // namespace ifkv

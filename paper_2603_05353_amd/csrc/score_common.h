@@ -1,0 +1,24 @@
+// Declarations shared by the two scoring translation units.
+#pragma once
+
+#include "ifkv_internal.h"
+
+namespace ifkv {
+
+// Largest number of query-row chunks the MFMA scoring pass splits one kv
+// head's (prompt row, query head) pairs into.
+constexpr int kMaxQChunks = 4;
+
+struct ScoreScratch {
+  size_t stats_off;    // float2 [H_q * M]: final (m, 1/Z)
+  size_t partial_off;  // float2 [slices][H_q * M]: per-slice (m, Z)
+  size_t colpart_off;  // float [H_kv * chunks][N]: partial column sums (MFMA pass B)
+  size_t total;
+};
+ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt);
+
+bool score_mfma_supported(const ifkv_ctx *ctx, int m_prompt);
+hipError_t launch_score_mfma(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
+                             int m_prompt, const void *k_prompt, int accumulate, float *scores);
+
+}  // namespace ifkv

@@ -1,0 +1,268 @@
+// Streaming stages: key re-rotation + cache assembly (stage 1), row splice
+// (stage 5) and the calibration copy.  All three are HBM-bound: every element
+// is read once and written once with 16-byte accesses, and each wavefront keeps
+// several independent loads in flight.
+#include "ifkv_device.h"
+#include "ifkv_internal.h"
+
+namespace ifkv {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRepoRows = 16;  // rows per tile
+constexpr int kBatch = 4;      // independent 16-byte loads in flight per thread and stream
+
+// ---------------------------------------------------------------------------
+// Stage 1.  Method, Eq. (5): global position = chunk start + local index; a
+// key cached at its local position reaches its global rotary phase when every
+// 2-D pair j is turned by advance * theta_j (Eq. 3-4; rotations add).
+// The advance is per chunk, so a block needs d/2 (cos, sin) values only; they
+// are formed in fp64 by the first d/2 threads and shared through LDS.
+// ---------------------------------------------------------------------------
+template <typename Tag, int PAIRING>
+__global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const double *__restrict__ inv_freq,
+                                                              int n_kv_heads, int head_dim,
+                                                              v4u *__restrict__ k_out,
+                                                              v4u *__restrict__ v_out) {
+  using E = Elem<Tag>;
+  constexpr int VE = E::kVec;
+  __shared__ float s_cos[kMaxHeadDim / 2];
+  __shared__ float s_sin[kMaxHeadDim / 2];
+
+  const int tile = blockIdx.x;
+  int ci = 0;
+  for (int i = 1; i < b.n; ++i)
+    if (tile >= b.c[i].tile0) ci = i;
+  const RepoChunk c = b.c[ci];
+  const int row0 = (tile - c.tile0) * kRepoRows;
+  const int nrows = min(kRepoRows, c.len - row0);
+  if (nrows <= 0) return;
+
+  const int tid = threadIdx.x;
+  const int half = head_dim / 2;
+  const bool identity = (c.advance == 0.0);
+  if (!identity && tid < half) {
+    double sn, cs;
+    sincos(c.advance * inv_freq[tid], &sn, &cs);
+    s_cos[tid] = static_cast<float>(cs);
+    s_sin[tid] = static_cast<float>(sn);
+  }
+  __syncthreads();
+
+  const int row_vecs = n_kv_heads * head_dim / VE;  // 16-byte vectors per row
+  const v4u *k_src = reinterpret_cast<const v4u *>(c.k) + static_cast<int64_t>(row0) * row_vecs;
+  v4u *k_dst = k_out + (c.dst_row + row0) * row_vecs;
+
+  if (identity) {
+    const int total = nrows * row_vecs;
+    for (int base = tid; base < total; base += kThreads * kBatch) {
+      v4u x[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) x[u] = __builtin_nontemporal_load(k_src + it);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) __builtin_nontemporal_store(x[u], k_dst + it);
+      }
+    }
+  } else if (PAIRING == IFKV_ROPE_HALF) {
+    const int hv = half / VE;            // vectors per half head
+    const int items_per_row = n_kv_heads * hv;
+    const int total = nrows * items_per_row;
+    for (int base = tid; base < total; base += kThreads * kBatch) {
+      v4u lo[kBatch], hi[kBatch];
+      int off[kBatch], cc[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) {
+          const int r = it / items_per_row;
+          const int w = it - r * items_per_row;
+          const int h = w / hv;
+          cc[u] = w - h * hv;
+          off[u] = r * row_vecs + h * 2 * hv + cc[u];
+          lo[u] = __builtin_nontemporal_load(k_src + off[u]);
+          hi[u] = __builtin_nontemporal_load(k_src + off[u] + hv);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) {
+          float a[VE], bb[VE], ra[VE], rb[VE];
+          E::unpack(lo[u], a);
+          E::unpack(hi[u], bb);
+#pragma unroll
+          for (int e = 0; e < VE; ++e) {
+            const float cs = s_cos[cc[u] * VE + e];
+            const float sn = s_sin[cc[u] * VE + e];
+            ra[e] = fmaf(a[e], cs, -(bb[e] * sn));
+            rb[e] = fmaf(a[e], sn, bb[e] * cs);
+          }
+          __builtin_nontemporal_store(E::pack(ra), k_dst + off[u]);
+          __builtin_nontemporal_store(E::pack(rb), k_dst + off[u] + hv);
+        }
+      }
+    }
+  } else {  // interleaved pairs (x_{2i}, x_{2i+1})
+    const int head_vecs = head_dim / VE;
+    const int total = nrows * row_vecs;
+    for (int base = tid; base < total; base += kThreads * kBatch) {
+      v4u x[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) x[u] = __builtin_nontemporal_load(k_src + it);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) {
+          const int pair0 = ((it % row_vecs) % head_vecs) * (VE / 2);
+          float f[VE], r[VE];
+          E::unpack(x[u], f);
+#pragma unroll
+          for (int e = 0; e < VE / 2; ++e) {
+            const float cs = s_cos[pair0 + e];
+            const float sn = s_sin[pair0 + e];
+            r[2 * e] = fmaf(f[2 * e], cs, -(f[2 * e + 1] * sn));
+            r[2 * e + 1] = fmaf(f[2 * e], sn, f[2 * e + 1] * cs);
+          }
+          __builtin_nontemporal_store(E::pack(r), k_dst + it);
+        }
+      }
+    }
+  }
+
+  // Values carry no rotary phase: plain row copy into the same rows.
+  if (c.v != nullptr && v_out != nullptr) {
+    const v4u *v_src = reinterpret_cast<const v4u *>(c.v) + static_cast<int64_t>(row0) * row_vecs;
+    v4u *v_dst = v_out + (c.dst_row + row0) * row_vecs;
+    const int total = nrows * row_vecs;
+    for (int base = tid; base < total; base += kThreads * kBatch) {
+      v4u x[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) x[u] = __builtin_nontemporal_load(v_src + it);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int it = base + u * kThreads;
+        if (it < total) __builtin_nontemporal_store(x[u], v_dst + it);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Stage 5.  "KV Recomputation": recomputed rows replace the cached rows of the
+// selected tokens.  One work item moves one 16-byte vector of one row.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void splice_kernel(const v4u *__restrict__ k_new,
+                                                          const v4u *__restrict__ v_new,
+                                                          const int32_t *__restrict__ idx, int64_t n_rows,
+                                                          int row_vecs, v4u *__restrict__ k_cache,
+                                                          v4u *__restrict__ v_cache, int64_t n_kv) {
+  const int64_t total = n_rows * row_vecs;
+  const int64_t base0 = static_cast<int64_t>(blockIdx.x) * (kThreads * kBatch) + threadIdx.x;
+  v4u xk[kBatch], xv[kBatch];
+  int64_t dst[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const int64_t it = base0 + u * kThreads;
+    dst[u] = -1;
+    if (it < total) {
+      const int64_t r = it / row_vecs;
+      const int w = static_cast<int>(it - r * row_vecs);
+      const int64_t row = idx[r];
+      if (row >= 0 && row < n_kv) {
+        dst[u] = row * row_vecs + w;
+        xk[u] = __builtin_nontemporal_load(k_new + it);
+        if (v_new != nullptr) xv[u] = __builtin_nontemporal_load(v_new + it);
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    if (dst[u] >= 0) {
+      k_cache[dst[u]] = xk[u];
+      if (v_new != nullptr) v_cache[dst[u]] = xv[u];
+    }
+  }
+}
+
+// Plain streaming copy with the same access shape (calibration only).
+__global__ __launch_bounds__(kThreads) void copy_kernel(v4u *__restrict__ dst, const v4u *__restrict__ src,
+                                                        int64_t n_vecs) {
+  const int64_t base0 = static_cast<int64_t>(blockIdx.x) * (kThreads * kBatch) + threadIdx.x;
+  v4u x[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const int64_t it = base0 + u * kThreads;
+    if (it < n_vecs) x[u] = __builtin_nontemporal_load(src + it);
+  }
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const int64_t it = base0 + u * kThreads;
+    if (it < n_vecs) __builtin_nontemporal_store(x[u], dst + it);
+  }
+}
+
+}  // namespace
+
+int reposition_rows_per_tile() { return kRepoRows; }
+
+hipError_t launch_reposition(ifkv_ctx *ctx, const RepoBatch &batch, void *k_out, void *v_out) {
+  if (batch.total_tiles <= 0) return hipSuccess;
+  const auto &d = ctx->desc;
+  dim3 grid(batch.total_tiles), block(kThreads);
+  v4u *ko = reinterpret_cast<v4u *>(k_out);
+  v4u *vo = reinterpret_cast<v4u *>(v_out);
+#define IFKV_LAUNCH_REPO(TAG, PAIR)                                                            \
+  hipLaunchKernelGGL((reposition_kernel<TAG, PAIR>), grid, block, 0, ctx->stream, batch,        \
+                     ctx->d_inv_freq, d.n_kv_heads, d.head_dim, ko, vo)
+  if (d.dtype == IFKV_BF16) {
+    if (d.pairing == IFKV_ROPE_HALF)
+      IFKV_LAUNCH_REPO(BF16Tag, IFKV_ROPE_HALF);
+    else
+      IFKV_LAUNCH_REPO(BF16Tag, IFKV_ROPE_INTERLEAVED);
+  } else {
+    if (d.pairing == IFKV_ROPE_HALF)
+      IFKV_LAUNCH_REPO(F32Tag, IFKV_ROPE_HALF);
+    else
+      IFKV_LAUNCH_REPO(F32Tag, IFKV_ROPE_INTERLEAVED);
+  }
+#undef IFKV_LAUNCH_REPO
+  return hipGetLastError();
+}
+
+hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, const int32_t *idx,
+                         int64_t n_rows, void *k_cache, void *v_cache, int64_t n_kv) {
+  if (n_rows <= 0) return hipSuccess;
+  const auto &d = ctx->desc;
+  const int row_vecs = static_cast<int>(d.n_kv_heads * d.head_dim * dtype_size(d.dtype) / 16);
+  const int64_t total = n_rows * row_vecs;
+  const int64_t per_block = kThreads * kBatch;
+  dim3 grid(static_cast<unsigned>((total + per_block - 1) / per_block)), block(kThreads);
+  hipLaunchKernelGGL(splice_kernel, grid, block, 0, ctx->stream, reinterpret_cast<const v4u *>(k_new),
+                     reinterpret_cast<const v4u *>(v_new), idx, n_rows, row_vecs,
+                     reinterpret_cast<v4u *>(k_cache), reinterpret_cast<v4u *>(v_cache), n_kv);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes) {
+  const int64_t n_vecs = n_bytes / 16;
+  if (n_vecs <= 0) return hipSuccess;
+  const int64_t per_block = kThreads * kBatch;
+  dim3 grid(static_cast<unsigned>((n_vecs + per_block - 1) / per_block)), block(kThreads);
+  hipLaunchKernelGGL(copy_kernel, grid, block, 0, ctx->stream, reinterpret_cast<v4u *>(dst),
+                     reinterpret_cast<const v4u *>(src), n_vecs);
+  return hipGetLastError();
+}
+
+}  // namespace ifkv

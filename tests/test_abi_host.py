@@ -1,0 +1,148 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects invalid arguments before any GPU call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_05353_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    with open(os.path.join(ROOT, "include", "ifkv.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ifkv_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2603_05353_amd.build import build_library
+        build_library()
+    return B.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    syms = header_symbols()
+    assert len(syms) >= 10
+    for s in syms:
+        assert hasattr(lib, s), s
+    assert set(syms) == set(B.EXPORTS)
+    assert lib.ifkv_version().decode().count(".") == 1
+
+
+def _layer(**kw):
+    args = dict(dtype="bf16", n_q_heads=32, n_kv_heads=8, head_dim=128, rope_theta=5e5,
+                max_ctx=4096, max_prompt=64)
+    args.update(kw)
+    return B.Layer(**args)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=30), dict(n_kv_heads=0), dict(head_dim=96), dict(rope_theta=-1.0),
+    dict(max_ctx=0), dict(max_ctx=1 << 31), dict(max_prompt=-1), dict(sm_scale=-0.5),
+])
+def test_create_rejects_bad_descriptors(lib, kw):
+    with pytest.raises(B.IfkvError) as e:
+        _layer(**kw)
+    assert e.value.code in (B.IFKV_EINVAL, B.IFKV_EDTYPE)
+    assert len(str(e.value)) > 20
+
+
+def test_create_ok_without_gpu(lib):
+    L = _layer()
+    L.close()
+    L.close()  # idempotent
+
+
+def _call(L, name, *args):
+    return getattr(L._lib, name)(L._ctx, *args)
+
+
+def test_reposition_validation(lib):
+    L = _layer()
+    fake = C.c_void_p(0x1000)  # never dereferenced: validation fails first
+    kp = (C.c_void_p * 3)(0x1000, 0x2000, 0x3000)
+    lens = (C.c_int32 * 3)(4, 4, 4)
+    bad_order = (C.c_int32 * 3)(0, 0, 1)
+    rc = _call(L, "ifkv_reposition_keys", 3, kp, None, lens, bad_order, None, None, fake, None, None, None)
+    assert rc == B.IFKV_EINVAL and b"permutation" in L._lib.ifkv_last_error(L._ctx)
+    neg = (C.c_int32 * 3)(4, -1, 4)
+    assert _call(L, "ifkv_reposition_keys", 3, kp, None, neg, None, None, None, fake, None, None, None) == B.IFKV_EINVAL
+    big = (C.c_int32 * 3)(4000, 4000, 4000)
+    assert _call(L, "ifkv_reposition_keys", 3, kp, None, big, None, None, None, fake, None, None, None) == B.IFKV_ESHAPE
+    assert _call(L, "ifkv_reposition_keys", -1, kp, None, lens, None, None, None, fake, None, None, None) == B.IFKV_EINVAL
+    nullk = (C.c_void_p * 3)(0x1000, None, 0x3000)
+    assert _call(L, "ifkv_reposition_keys", 3, nullk, None, lens, None, None, None, fake, None, None, None) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_reposition_keys", 3, kp, None, lens, None, None, None, None, None, None, None) == B.IFKV_EINVAL
+    unaligned = (C.c_void_p * 3)(0x1004, 0x2000, 0x3000)
+    assert _call(L, "ifkv_reposition_keys", 3, unaligned, None, lens, None, None, None, fake, None, None, None) == B.IFKV_EINVAL
+    # host outputs are valid even when nothing has to run: all chunks empty
+    zero = (C.c_int32 * 3)(0, 0, 0)
+    starts = (C.c_int64 * 3)(7, 7, 7)
+    n = C.c_int64(-1)
+    assert _call(L, "ifkv_reposition_keys", 3, kp, None, zero, None, None, None, None, None, starts, C.byref(n)) == B.IFKV_OK
+    assert list(starts) == [0, 0, 0] and n.value == 0
+    L.close()
+
+
+def test_score_validation(lib):
+    L = _layer()
+    f = C.c_void_p(0x1000)
+    assert _call(L, "ifkv_score_tokens", f, 5000, f, 8, None, 0, f) == B.IFKV_ESHAPE
+    assert _call(L, "ifkv_score_tokens", f, 100, f, 65, None, 0, f) == B.IFKV_ESHAPE
+    assert _call(L, "ifkv_score_tokens", f, -1, f, 8, None, 0, f) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_score_tokens", f, 100, f, 8, None, 0, None) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_score_tokens", None, 100, f, 8, None, 0, f) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_score_tokens", f, 0, f, 8, None, 0, f) == B.IFKV_OK
+    L.close()
+
+
+def test_topk_validation_and_budget(lib):
+    L = _layer()
+    f = C.c_void_p(0x1000)
+    k = C.c_int64(-1)
+    assert _call(L, "ifkv_select_topk", f, 100, 1.5, -1, f, C.byref(k)) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_select_topk", f, 100, -0.1, -1, f, C.byref(k)) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_select_topk", f, 100, float("nan"), -1, f, C.byref(k)) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_select_topk", f, 100, 0.5, 101, f, C.byref(k)) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_select_topk", f, 5000, 0.5, -1, f, C.byref(k)) == B.IFKV_ESHAPE
+    # k = floor(rho N) is known on the host; k = 0 launches nothing
+    assert _call(L, "ifkv_select_topk", f, 100, 0.0, -1, f, C.byref(k)) == B.IFKV_OK and k.value == 0
+    assert _call(L, "ifkv_select_topk", f, 6, 0.15, -1, f, C.byref(k)) == B.IFKV_OK and k.value == 0
+    assert _call(L, "ifkv_select_topk", None, 1024, 0.15, -1, None, C.byref(k)) == B.IFKV_EINVAL and k.value == 153
+    L.close()
+
+
+def test_attention_and_splice_validation(lib):
+    L = _layer()
+    f = C.c_void_p(0x1000)
+    assert _call(L, "ifkv_recompute_attention", f, f, 4, f, f, 5000, f, None) == B.IFKV_ESHAPE
+    assert _call(L, "ifkv_recompute_attention", f, f, -4, f, f, 100, f, None) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_recompute_attention", f, f, 4, f, f, 0, f, None) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_recompute_attention", f, None, 4, f, f, 100, f, None) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_recompute_attention", f, f, 0, f, f, 100, f, None) == B.IFKV_OK
+    assert _call(L, "ifkv_splice_kv", f, f, f, 4, f, None, 100) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_splice_kv", f, f, None, 4, f, f, 100) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_splice_kv", f, f, f, 0, f, f, 100) == B.IFKV_OK
+    assert _call(L, "ifkv_splice_kv", f, f, f, 4, f, f, 5000) == B.IFKV_ESHAPE
+    assert _call(L, "ifkv_copy_bytes", f, f, 24) == B.IFKV_EINVAL
+    assert _call(L, "ifkv_copy_bytes", f, f, 0) == B.IFKV_OK
+    L.close()
+
+
+def test_product_does_not_import_oracle():
+    """The HIP path must not route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2603_05353_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                with open(os.path.join(dirpath, fn)) as f:
+                    text = f.read()
+                assert "oracle" not in text.lower(), fn
+    with open(os.path.join(ROOT, "oracle", "infoflow_oracle.py")) as f:
+        assert "paper_2603_05353_amd" not in f.read().replace("from the product", "")

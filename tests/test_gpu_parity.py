@@ -1,0 +1,461 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against
+the fp64 CPU oracle on the same seeded inputs.
+
+Tolerances (stated per test):
+  stage 1  fp32: 2e-6 * |pair| ; bf16: half a bf16 ulp of the exact value (one
+           rounding to storage) + 2e-6 * |pair| for the fp32 rotation
+  stage 2  |s - s_ref| <= rtol * (|s_ref| + M/N), rtol 1e-5 (fp32) / 1e-2 (bf16)
+  stage 3  bit-exact on identical fp32 input
+  stage 4  max-abs 1e-4 (fp32) / 2e-2 (bf16)
+  stage 5  bit-exact
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import infoflow_oracle as O
+from tests.helpers import (DEV, bf16_ulp, make_layer, score_tol, to_dev, to_host_bits, to_host_f64)
+from workloads import make_recompute_inputs, make_workload, preset, to_f64, to_storage
+
+pytestmark = pytest.mark.gpu
+
+FORCE_GENERIC = 1
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+def oracle_inputs(wl):
+    sp = wl.spec
+    k = [to_f64(c, sp.dtype) for c in wl.k_chunks]
+    v = [to_f64(c, sp.dtype) for c in wl.v_chunks]
+    return k, v, to_f64(wl.q_prompt, sp.dtype)
+
+
+def dev_chunks(wl):
+    sp = wl.spec
+    shape = (0, sp.n_kv_heads, sp.head_dim)
+    kd = [to_dev(c.reshape(-1, *shape[1:]), sp.dtype) for c in wl.k_chunks]
+    vd = [to_dev(c.reshape(-1, *shape[1:]), sp.dtype) for c in wl.v_chunks]
+    return kd, vd
+
+
+def check_reposition(k_gpu, K_ref, dtype, half):
+    """Element-wise bound described in the module docstring."""
+    if half == "half":
+        d = K_ref.shape[-1]
+        pair = np.hypot(K_ref[..., : d // 2], K_ref[..., d // 2:])
+        pair = np.concatenate([pair, pair], axis=-1)
+    else:
+        pr = np.hypot(K_ref[..., 0::2], K_ref[..., 1::2])
+        pair = np.repeat(pr, 2, axis=-1)
+    err = np.abs(k_gpu - K_ref)
+    bound = 2e-6 * pair + 1e-30
+    if dtype == "bf16":
+        bound = bound + 0.5 * bf16_ulp(K_ref) * 1.001
+    worst = (err - bound).max()
+    assert worst <= 0, f"reposition error exceeds bound by {worst}"
+
+
+# ---------------------------------------------------------------------------
+# stage 1
+# ---------------------------------------------------------------------------
+REPO_CASES = [
+    ("C1-full", preset("C1")),
+    ("C2-ragged", preset("C2", chunk_lens=[70, 0, 33, 129, 16, 1], m_prompt=8)),
+    ("C3-permuted", preset("C3", chunk_lens=[96] * 8, m_prompt=8)),
+    ("C4-uneven", preset("C4", uneven=(12, 20, 90), m_prompt=8)),
+    ("C5-vlm", preset("C5", chunk_lens=[40] * 16 + [24] * 8, m_prompt=8)),
+    ("interleaved-bf16", preset("C2", chunk_lens=[50, 31, 64], m_prompt=8, pairing="interleaved")),
+    ("interleaved-f32", preset("C1", chunk_lens=[50, 31, 64], m_prompt=8, pairing="interleaved")),
+    ("many-chunks", preset("C3", chunk_lens=[5] * 70 + [17] * 3, m_prompt=8)),   # > 64 chunks: two launches
+]
+
+
+@pytest.mark.parametrize("name,spec", REPO_CASES, ids=[c[0] for c in REPO_CASES])
+def test_reposition_parity(name, spec):
+    wl = make_workload(spec)
+    k, v, _ = oracle_inputs(wl)
+    K_ref, V_ref, start_ref, N = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, spec.pairing)
+    L = make_layer(spec, max_ctx=max(N, 1), max_prompt=8)
+    kd, vd = dev_chunks(wl)
+    k_out, v_out, starts, n_ctx = L.reposition_keys(kd, vd, chunk_order=wl.chunk_order.tolist())
+    sync()
+    assert n_ctx == N and starts == start_ref.tolist()
+    check_reposition(to_host_f64(k_out, spec.dtype), K_ref, spec.dtype, spec.pairing)
+    # values: exact gather
+    assert np.array_equal(to_host_f64(v_out, spec.dtype), V_ref)
+    # the chunk in the first slot is not rotated at all: bit-identical
+    c0 = int(wl.chunk_order[0])
+    L0 = int(wl.chunk_len[c0])
+    assert np.array_equal(to_host_bits(k_out[:L0], spec.dtype).ravel(),
+                          to_host_bits(kd[c0], spec.dtype).ravel())
+    # keys-only call leaves v untouched and gives the same keys
+    k2, v2, _, _ = L.reposition_keys(kd, None, chunk_order=wl.chunk_order.tolist())
+    sync()
+    assert v2 is None and torch.equal(k2.view(torch.int16 if spec.dtype == "bf16" else torch.int32),
+                                      k_out.view(torch.int16 if spec.dtype == "bf16" else torch.int32))
+    L.close()
+
+
+def test_reposition_pos0_and_override():
+    spec = preset("C2", chunk_lens=[40, 25, 64], m_prompt=8)
+    wl = make_workload(spec)
+    k, v, _ = oracle_inputs(wl)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8)
+    kd, vd = dev_chunks(wl)
+    pos0 = [3, 100, 7]
+    K_ref, _, _, _ = O.reposition_keys(k, None, wl.chunk_len, None, spec.rope_theta, cached_pos0=pos0)
+    k_out, _, _, _ = L.reposition_keys(kd, None, cached_pos0=pos0)
+    sync()
+    check_reposition(to_host_f64(k_out, "bf16"), K_ref, "bf16", "half")
+    over = [0, 0, 129]
+    K_ref, _, _, _ = O.reposition_keys(k, None, wl.chunk_len, None, spec.rope_theta, delta_override=over)
+    k_out, _, _, _ = L.reposition_keys(kd, None, delta_override=over)
+    sync()
+    check_reposition(to_host_f64(k_out, "bf16"), K_ref, "bf16", "half")
+    L.close()
+
+
+def test_reposition_large_delta_angles():
+    """Phase advances of ~130K positions: angles must be formed in fp64."""
+    spec = preset("C1", chunk_lens=[8, 24], m_prompt=8)
+    wl = make_workload(spec)
+    k, _, _ = oracle_inputs(wl)
+    over = [131000, 98765]
+    K_ref, _, _, _ = O.reposition_keys(k, None, wl.chunk_len, None, spec.rope_theta, delta_override=over)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8)
+    kd, _ = dev_chunks(wl)
+    k_out, _, _, _ = L.reposition_keys(kd, None, delta_override=over)
+    sync()
+    check_reposition(to_host_f64(k_out, "f32"), K_ref, "f32", "half")
+    L.close()
+
+
+# ---------------------------------------------------------------------------
+# stage 2
+# ---------------------------------------------------------------------------
+def global_keys(wl):
+    """Oracle-side global-frame keys, rounded to the storage dtype so both
+    sides score exactly the same stored values."""
+    sp = wl.spec
+    k, _, q = oracle_inputs(wl)
+    K, _, _, N = O.reposition_keys(k, None, wl.chunk_len, wl.chunk_order, sp.rope_theta, sp.pairing)
+    K_st = to_storage(K, sp.dtype)
+    return K_st, to_f64(K_st, sp.dtype), q
+
+
+SCORE_CASES = [
+    ("C1-full", preset("C1"), 0, 1e-5),
+    ("C2-small-alu", preset("C2", chunk_lens=[200, 77, 301], m_prompt=19), FORCE_GENERIC, 1e-2),
+    ("C2-small", preset("C2", chunk_lens=[200, 77, 301], m_prompt=19), 0, 1e-2),
+    ("C3-small", preset("C3", chunk_lens=[130] * 9, m_prompt=40), 0, 1e-2),
+    ("C4-small", preset("C4", uneven=(10, 50, 150), m_prompt=33), 0, 1e-2),
+    ("C5-small", preset("C5", chunk_lens=[64] * 16 + [32] * 8, m_prompt=24), 0, 1e-2),
+    ("d64-bf16", preset("C2", head_dim=64, n_q_heads=8, n_kv_heads=4, chunk_lens=[100, 50], m_prompt=7), 0, 1e-2),
+]
+
+
+@pytest.mark.parametrize("name,spec,flags,rtol", SCORE_CASES, ids=[c[0] for c in SCORE_CASES])
+def test_score_parity(name, spec, flags, rtol):
+    wl = make_workload(spec)
+    K_st, K64, q64 = global_keys(wl)
+    s_ref = O.score_tokens(K64, q64, wl.sm_scale)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=spec.m_prompt, flags=flags)
+    kd = to_dev(K_st, spec.dtype)
+    qd = to_dev(wl.q_prompt, spec.dtype)
+    s = L.score_tokens(kd, qd)
+    sync()
+    s = s.cpu().numpy().astype(np.float64)
+    assert (np.abs(s - s_ref) <= score_tol(s_ref, spec.m_prompt, rtol)).all(), \
+        f"max rel {np.max(np.abs(s - s_ref) / (np.abs(s_ref) + spec.m_prompt / wl.n_ctx))}"
+    assert abs(s.sum() - spec.m_prompt) < 1e-3 * spec.m_prompt
+    # accumulate adds on top
+    s2 = L.score_tokens(kd, qd, scores=torch.from_numpy(s_ref.astype(np.float32)).to(DEV), accumulate=True)
+    sync()
+    assert (np.abs(s2.cpu().numpy() - 2 * s_ref) <= 2 * score_tol(s_ref, spec.m_prompt, rtol)).all()
+    L.close()
+
+
+@pytest.mark.parametrize("flags", [0, FORCE_GENERIC], ids=["default", "alu"])
+def test_score_with_prompt_keys(flags):
+    spec = preset("C2", chunk_lens=[90, 41], m_prompt=12)
+    wl = make_workload(spec)
+    K_st, K64, q64 = global_keys(wl)
+    g = np.random.Generator(np.random.Philox(key=[5, 5]))
+    kp = to_storage(g.standard_normal((spec.m_prompt, spec.n_kv_heads, spec.head_dim)) * 0.3, "bf16")
+    s_ref = O.score_tokens(K64, q64, wl.sm_scale, k_prompt=to_f64(kp, "bf16"))
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=spec.m_prompt, flags=flags)
+    s = L.score_tokens(to_dev(K_st, "bf16"), to_dev(wl.q_prompt, "bf16"), k_prompt=to_dev(kp, "bf16"))
+    sync()
+    s = s.cpu().numpy().astype(np.float64)
+    assert (np.abs(s - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all()
+    assert s.sum() < spec.m_prompt
+    L.close()
+
+
+def test_score_peaky_logits():
+    """Logits with a spread of ~+-12: exercises the running max / rescaling."""
+    spec = preset("C2", chunk_lens=[300, 211], m_prompt=16, sigma=0.55)
+    wl = make_workload(spec)
+    K_st, K64, q64 = global_keys(wl)
+    s_ref = O.score_tokens(K64, q64, wl.sm_scale)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=spec.m_prompt)
+    s = L.score_tokens(to_dev(K_st, "bf16"), to_dev(wl.q_prompt, "bf16"))
+    sync()
+    s = s.cpu().numpy().astype(np.float64)
+    assert s_ref.max() > 20 * s_ref.mean()
+    assert (np.abs(s - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all()
+    L.close()
+
+
+# ---------------------------------------------------------------------------
+# stage 3
+# ---------------------------------------------------------------------------
+def topk_case(n, kind, seed):
+    g = np.random.Generator(np.random.Philox(key=[seed, n]))
+    if kind == "uniform":
+        s = g.random(n)
+    elif kind == "ties":
+        s = g.integers(0, 7, size=n) * 0.125
+    elif kind == "equal":
+        s = np.full(n, 0.0078125)
+    elif kind == "signed":
+        s = g.standard_normal(n)
+        s[:: 5] = 0.0
+        s[1:: 7] = -0.0
+    elif kind == "near-uniform":        # what near-uniform attention produces
+        s = 0.0078125 * (1 + 1e-6 * g.standard_normal(n))
+    else:
+        raise ValueError(kind)
+    return s.astype(np.float32)
+
+
+@pytest.mark.parametrize("n", [1, 5, 63, 1000, 8192, 8193, 20000, 32768, 32769, 50000, 140001])
+@pytest.mark.parametrize("kind", ["uniform", "ties", "equal", "signed", "near-uniform"])
+def test_topk_bit_exact(n, kind):
+    s = topk_case(n, kind, 77)
+    spec = preset("C1")
+    L = make_layer(spec, max_ctx=max(n, 1), max_prompt=8)
+    sd = torch.from_numpy(s).to(DEV)
+    for k in sorted({0, 1, n // 7, int(0.15 * n), n - 1, n}):
+        if k < 0:
+            continue
+        idx = L.select_topk(sd, k=k)
+        sync()
+        ref = O.select_topk(s, k)
+        assert idx.dtype == torch.int32 and idx.numel() == k
+        assert np.array_equal(idx.cpu().numpy().astype(np.int64), ref), (n, kind, k)
+    # ratio form
+    idx = L.select_topk(sd, ratio=0.15)
+    sync()
+    assert np.array_equal(idx.cpu().numpy().astype(np.int64), O.select_topk(s, O.budget(n, 0.15)))
+    L.close()
+
+
+def test_topk_unaligned_input():
+    s = topk_case(9000, "uniform", 3)
+    spec = preset("C1")
+    L = make_layer(spec, max_ctx=9000, max_prompt=8)
+    buf = torch.zeros(9001, dtype=torch.float32, device=DEV)
+    buf[1:] = torch.from_numpy(s).to(DEV)
+    idx = L.select_topk(buf[1:], k=1234)
+    sync()
+    assert np.array_equal(idx.cpu().numpy().astype(np.int64), O.select_topk(s, 1234))
+    L.close()
+
+
+# ---------------------------------------------------------------------------
+# stage 4
+# ---------------------------------------------------------------------------
+def attention_case(spec, rows, seed=0, flags=0, q_gain=1.0):
+    """Runs both sides on the spec's workload for the given selected rows."""
+    wl = make_workload(spec)
+    K_st, K64, _ = global_keys(wl)
+    V_st = np.concatenate([wl.v_chunks[c] for c in wl.chunk_order], axis=0)
+    V64 = to_f64(V_st, spec.dtype)
+    rows = np.asarray(rows, dtype=np.int64)
+    q_sel, _, _ = make_recompute_inputs(wl, rows)
+    if q_gain != 1.0:
+        q_sel = to_storage(to_f64(q_sel, spec.dtype) * q_gain, spec.dtype)
+    q64 = to_f64(q_sel, spec.dtype)
+    ref, lse_ref = O.recompute_attention(q64, rows, K64, V64, wl.sm_scale)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8, flags=flags)
+    out, lse = L.recompute_attention(to_dev(q_sel, spec.dtype), torch.from_numpy(rows.astype(np.int32)).to(DEV),
+                                     to_dev(K_st, spec.dtype), to_dev(V_st, spec.dtype), return_lse=True)
+    sync()
+    L.close()
+    return to_host_f64(out, spec.dtype), lse.cpu().numpy().astype(np.float64), ref, lse_ref
+
+
+def sample_rows(n_ctx, k, seed):
+    g = np.random.Generator(np.random.Philox(key=[seed, 11]))
+    return np.sort(g.choice(n_ctx, size=k, replace=False))
+
+
+def test_attention_c1_fp32():
+    spec = preset("C1")
+    rows = sample_rows(1024, 153, 1)
+    rows[0] = 0
+    out, lse, ref, lse_ref = attention_case(spec, np.unique(rows))
+    assert np.abs(out - ref).max() <= 1e-4
+    assert np.abs(lse - lse_ref).max() <= 1e-4
+
+
+ATTN_CASES = [
+    ("C2-ragged", preset("C2", chunk_lens=[333, 120, 250], m_prompt=8), 105, 0),
+    ("C2-ragged-alu", preset("C2", chunk_lens=[333, 120, 250], m_prompt=8), 105, FORCE_GENERIC),
+    ("C3-small", preset("C3", chunk_lens=[100] * 11, m_prompt=8), 165, 0),
+    ("C4-small", preset("C4", uneven=(9, 60, 180), m_prompt=8), 97, 0),
+    ("C5-gqa7", preset("C5", chunk_lens=[64] * 16 + [32] * 8, m_prompt=8), 192, 0),
+    ("few-rows", preset("C2", chunk_lens=[500], m_prompt=8), 3, 0),
+    ("many-rows-big-blocks", preset("C2", chunk_lens=[640] * 8, m_prompt=8), 4200, 0),
+]
+
+
+@pytest.mark.parametrize("name,spec,k,flags", ATTN_CASES, ids=[c[0] for c in ATTN_CASES])
+def test_attention_parity_bf16(name, spec, k, flags):
+    n_ctx = int(np.sum(spec.chunk_lens)) if spec.chunk_lens is not None else make_workload(spec).n_ctx
+    rows = sample_rows(n_ctx, min(k, n_ctx), 2)
+    if name == "many-rows-big-blocks":
+        # the oracle checks a subsample of rows (rows are independent)
+        out, lse, ref, lse_ref = attention_case_subsampled(spec, rows, 300)
+    else:
+        out, lse, ref, lse_ref = attention_case(spec, rows, flags=flags)
+    assert np.abs(out - ref).max() <= 2e-2, np.abs(out - ref).max()
+    assert np.abs(lse - lse_ref).max() <= 2e-2
+
+
+def attention_case_subsampled(spec, rows, n_check):
+    wl = make_workload(spec)
+    K_st, K64, _ = global_keys(wl)
+    V_st = np.concatenate([wl.v_chunks[c] for c in wl.chunk_order], axis=0)
+    V64 = to_f64(V_st, spec.dtype)
+    q_sel, _, _ = make_recompute_inputs(wl, rows)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8)
+    out, lse = L.recompute_attention(to_dev(q_sel, spec.dtype), torch.from_numpy(rows.astype(np.int32)).to(DEV),
+                                     to_dev(K_st, spec.dtype), to_dev(V_st, spec.dtype), return_lse=True)
+    sync()
+    L.close()
+    g = np.random.Generator(np.random.Philox(key=[9, 9]))
+    pick = np.sort(np.unique(np.concatenate([[0, 1, len(rows) - 1], g.choice(len(rows), n_check, replace=False)])))
+    ref, lse_ref = O.recompute_attention(to_f64(q_sel, spec.dtype)[pick], rows[pick], K64, V64, wl.sm_scale)
+    return to_host_f64(out, spec.dtype)[pick], lse.cpu().numpy().astype(np.float64)[pick], ref, lse_ref
+
+
+def test_attention_full_ratio_is_dense_causal():
+    spec = preset("C2", chunk_lens=[150, 83], m_prompt=8)
+    out, lse, ref, lse_ref = attention_case(spec, np.arange(233))
+    assert np.abs(out - ref).max() <= 2e-2
+    # first row attends to itself only: output is V[0] up to the bf16 rounding of P = 1
+    assert np.abs(lse - lse_ref).max() <= 2e-2
+
+
+def test_attention_peaky_logits():
+    spec = preset("C2", chunk_lens=[700, 301], m_prompt=8, sigma=0.3)
+    rows = sample_rows(1001, 150, 4)
+    out, lse, ref, lse_ref = attention_case(spec, rows, q_gain=6.0)
+    assert np.abs(out - ref).max() <= 2e-2
+    assert np.abs(lse - lse_ref).max() <= 2e-2
+
+
+def test_attention_out_of_range_rows_give_zeros():
+    spec = preset("C2", chunk_lens=[128], m_prompt=8)
+    wl = make_workload(spec)
+    K_st, K64, _ = global_keys(wl)
+    V_st = wl.v_chunks[0]
+    rows = np.array([5, 60, 127], dtype=np.int64)
+    q_sel, _, _ = make_recompute_inputs(wl, rows)
+    bad = torch.tensor([5, 128, -1], dtype=torch.int32, device=DEV)
+    L = make_layer(spec, max_ctx=128, max_prompt=8)
+    out = L.recompute_attention(to_dev(q_sel, "bf16"), bad, to_dev(K_st, "bf16"), to_dev(V_st, "bf16"))
+    sync()
+    o = to_host_f64(out, "bf16")
+    assert np.abs(o[0]).max() > 0 and np.array_equal(o[1:], np.zeros_like(o[1:]))
+    L.close()
+
+
+# ---------------------------------------------------------------------------
+# stage 5
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", ["C1", "C2"])
+def test_splice_bit_exact(cfg):
+    spec = preset(cfg) if cfg == "C1" else preset("C2", chunk_lens=[300, 211], m_prompt=8)
+    wl = make_workload(spec)
+    K_st, _, _ = global_keys(wl)
+    V_st = np.concatenate([wl.v_chunks[c] for c in wl.chunk_order], axis=0)
+    idx = sample_rows(wl.n_ctx, O.budget(wl.n_ctx, 0.15), 6)
+    _, k_new, v_new = make_recompute_inputs(wl, idx)
+    Kr, Vr = O.splice_kv(K_st, V_st, k_new, v_new, idx)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8)
+    kd, vd = to_dev(K_st, spec.dtype), to_dev(V_st, spec.dtype)
+    idx_d = torch.from_numpy(idx.astype(np.int32)).to(DEV)
+    L.splice_kv(to_dev(k_new, spec.dtype), to_dev(v_new, spec.dtype), idx_d, kd, vd)
+    sync()
+    bits = np.uint16 if spec.dtype == "bf16" else np.uint32
+    assert np.array_equal(to_host_bits(kd, spec.dtype), np.ascontiguousarray(Kr).view(bits))
+    assert np.array_equal(to_host_bits(vd, spec.dtype), np.ascontiguousarray(Vr).view(bits))
+    # keys only; and rows outside the cache are skipped
+    kd2 = to_dev(K_st, spec.dtype)
+    idx2 = idx_d.clone()
+    idx2[0] = wl.n_ctx + 5
+    L.splice_kv(to_dev(k_new, spec.dtype), None, idx2, kd2, None)
+    sync()
+    Kr2, _ = O.splice_kv(K_st, V_st, k_new[1:], v_new[1:], idx[1:])
+    assert np.array_equal(to_host_bits(kd2, spec.dtype), np.ascontiguousarray(Kr2).view(bits))
+    L.close()
+
+
+# ---------------------------------------------------------------------------
+# composite
+# ---------------------------------------------------------------------------
+def run_layer_gpu(wl, ratio, flags=0):
+    sp = wl.spec
+    L = make_layer(sp, max_ctx=wl.n_ctx, max_prompt=sp.m_prompt, flags=flags)
+    kd, vd = dev_chunks(wl)
+    K, V, starts, N = L.reposition_keys(kd, vd, chunk_order=wl.chunk_order.tolist())
+    s = L.score_tokens(K, to_dev(wl.q_prompt, sp.dtype))
+    idx = L.select_topk(s, ratio=ratio)
+    sync()
+    return L, K, V, s, idx
+
+
+@pytest.mark.parametrize("cfg,rtol_sel", [("C1", 1e-5), ("C2", 1e-4)])
+def test_composite_layer(cfg, rtol_sel):
+    """Whole path, in the order: reposition, score, select, splice, attend."""
+    spec = preset(cfg) if cfg == "C1" else preset("C2", chunk_lens=[256] * 6, m_prompt=32)
+    wl = make_workload(spec)
+    k, v, q = oracle_inputs(wl)
+    ratio = 0.15
+    L, K, V, s, idx = run_layer_gpu(wl, ratio)
+    # oracle on its own
+    Kref, Vref, _, N = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, spec.pairing)
+    s_ref = O.score_tokens(Kref, q, wl.sm_scale)
+    kk = O.budget(N, ratio)
+    idx_ref = O.select_topk(s_ref, kk)
+    # (i) the GPU selection is exact for the GPU's own fp32 scores
+    s_gpu = s.cpu().numpy()
+    idx_gpu = idx.cpu().numpy().astype(np.int64)
+    assert np.array_equal(idx_gpu, O.select_topk(s_gpu, kk))
+    # (ii) against the oracle's set: only tokens within tolerance of the threshold may differ
+    thr = np.sort(s_ref)[::-1][kk - 1]
+    near = np.abs(s_ref - thr) <= rtol_sel * (thr + spec.m_prompt / N)
+    diff = np.setxor1d(idx_gpu, idx_ref)
+    assert near[diff].all(), f"{len(diff)} differing tokens, not all near the threshold"
+    planted_clear = [j for j in wl.planted if s_ref[j] - thr > rtol_sel * (thr + spec.m_prompt / N)]
+    assert set(planted_clear) <= set(idx_gpu.tolist())
+    # stages 5 and 4 on the oracle's selection (inputs never come from the GPU path)
+    q_sel, k_new, v_new = make_recompute_inputs(wl, idx_ref)
+    idx_d = torch.from_numpy(idx_ref.astype(np.int32)).to(DEV)
+    L.splice_kv(to_dev(k_new, spec.dtype), to_dev(v_new, spec.dtype), idx_d, K, V)
+    out, lse = L.recompute_attention(to_dev(q_sel, spec.dtype), idx_d, K, V, return_lse=True)
+    sync()
+    # oracle: the same on the GPU-independent side, with stage-1 output rounded to storage
+    K_st, V_st = to_storage(Kref, spec.dtype), to_storage(Vref, spec.dtype)
+    K2, V2 = O.splice_kv(to_f64(K_st, spec.dtype), to_f64(V_st, spec.dtype),
+                         to_f64(k_new, spec.dtype), to_f64(v_new, spec.dtype), idx_ref)
+    ref, _ = O.recompute_attention(to_f64(q_sel, spec.dtype), idx_ref, K2, V2, wl.sm_scale)
+    tol = 1e-4 if spec.dtype == "f32" else 2e-2
+    assert np.abs(to_host_f64(out, spec.dtype) - ref).max() <= tol
+    L.close()
