@@ -16,4 +16,5 @@ from .synth import (  # noqa: F401
     preset,
     rope_at,
     to_f64,
+    to_storage,
 )
