@@ -189,7 +189,7 @@ def main():
     print(json.dumps(result))
 
 
-def cpu_baseline(wl, ratio, q_sel, k_new, v_new, n_rows_sample=64):
+def cpu_baseline(wl, ratio, q_sel, k_new, v_new, n_rows_sample=1536):
     """Stages 1, 2, 3, 5 in full; stage 4 on a seeded sample of rows (rows are
     independent), extrapolated by the causal work sum_r (p_r + 1)."""
     from oracle import infoflow_oracle as O

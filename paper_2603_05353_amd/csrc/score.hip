@@ -225,7 +225,19 @@ hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, cons
   }
   const bool generic = (d.flags & IFKV_FLAG_FORCE_GENERIC) || d.dtype != IFKV_BF16 || d.head_dim != 128 ||
                        !score_mfma_supported(ctx, m_prompt);
-  if (!generic) return launch_score_mfma(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
+  if (!generic) {
+    // MFMA sweeps around the same merge kernel (which also folds in the prompt keys)
+    int n_slices = 0;
+    hipError_t e = launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, false, 0, nullptr);
+    if (e != hipSuccess) return e;
+    ScoreScratch sc = score_scratch_layout(ctx, n_ctx, m_prompt);
+    float2 *partial = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.partial_off);
+    float2 *stats = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.stats_off);
+    const int rows = d.n_q_heads * m_prompt;
+    hipLaunchKernelGGL((score_merge_kernel<BF16Tag, 128>), dim3((rows + 127) / 128), dim3(128), 0, ctx->stream, partial,
+                       n_slices, q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
+    return launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, true, accumulate, scores);
+  }
   if (d.dtype == IFKV_BF16) {
     if (d.head_dim == 128) return run_generic<BF16Tag, 128>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);
     return run_generic<BF16Tag, 64>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);

@@ -18,7 +18,9 @@ struct ScoreScratch {
 ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt);
 
 bool score_mfma_supported(const ifkv_ctx *ctx, int m_prompt);
-hipError_t launch_score_mfma(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
-                             int m_prompt, const void *k_prompt, int accumulate, float *scores);
+// pass_b == false: per-block partial (max, sum) of every (head, prompt row); *n_slices_out = number of
+// partials per row.  pass_b == true: column sums with the merged statistics, reduced into `scores`.
+hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
+                                    int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores);
 
 }  // namespace ifkv

@@ -196,8 +196,8 @@ def test_score_with_prompt_keys(flags):
 
 
 def test_score_peaky_logits():
-    """Logits with a spread of ~+-12: exercises the running max / rescaling."""
-    spec = preset("C2", chunk_lens=[300, 211], m_prompt=16, sigma=0.55)
+    """Logits with a standard deviation of ~4: exercises the running max / rescaling."""
+    spec = preset("C2", chunk_lens=[300, 211], m_prompt=16, sigma=2.0)
     wl = make_workload(spec)
     K_st, K64, q64 = global_keys(wl)
     s_ref = O.score_tokens(K64, q64, wl.sm_scale)
@@ -205,7 +205,7 @@ def test_score_peaky_logits():
     s = L.score_tokens(to_dev(K_st, "bf16"), to_dev(wl.q_prompt, "bf16"))
     sync()
     s = s.cpu().numpy().astype(np.float64)
-    assert s_ref.max() > 20 * s_ref.mean()
+    assert s_ref.max() > 3 * s_ref.mean()
     assert (np.abs(s - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all()
     L.close()
 
