@@ -46,6 +46,10 @@ def parse():
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-iters", type=int, default=20)
+    ap.add_argument("--only", default=None,
+                    choices=["reposition_keys", "score_tokens", "select_topk", "splice_kv",
+                             "recompute_attention", "copy"],
+                    help="profiling aid: after set-up run only this stage --stage-iters times and exit")
     return ap.parse_args()
 
 
@@ -103,6 +107,25 @@ def main():
     q_sel_d, k_new_d, v_new_d = dev_t(q_sel), dev_t(k_new), dev_t(v_new)
     out = torch.empty(k_sel, spec.n_q_heads, spec.head_dim, dtype=tdt, device=dev)
     idx_k = idx[:k_sel]
+
+    if args.only is not None:
+        src = torch.empty(2 * N * spec.n_kv_heads * spec.head_dim * e, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        fn = {
+            "reposition_keys": lambda: L.reposition_keys(kd, vd, chunk_order=order, k_out=K, v_out=V),
+            "score_tokens": lambda: L.score_tokens(K, qd, scores=scores),
+            "select_topk": lambda: L.select_topk(scores, ratio=ratio, idx_out=idx),
+            "splice_kv": lambda: L.splice_kv(k_new_d, v_new_d, idx_k, K, V),
+            "recompute_attention": lambda: L.recompute_attention(q_sel_d, idx_k, K, V, out=out),
+            "copy": lambda: L.copy_bytes(dst, src),
+        }[args.only]
+        for _ in range(args.stage_iters):
+            fn()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "iters": args.stage_iters, "workload": args.workload,
+                          "ratio": ratio, "copy_bytes": int(src.numel())}))
+        L.close()
+        return
 
     def step():
         L.reposition_keys(kd, vd, chunk_order=order, k_out=K, v_out=V)

@@ -20,6 +20,8 @@
 // order (sigma below): no LDS round trip for P.
 // V is transposed on its way into LDS (8x8 register transposes) because the
 // second product contracts over kv, which is the strided axis of the cache.
+#include <cstdlib>
+
 #include "attention_common.h"
 #include "ifkv_device.h"
 
@@ -61,8 +63,9 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   constexpr int KPT = (TK * D / 8 + KTHREADS - 1) / KTHREADS;  // 16-byte K vectors per staging thread
   static_assert(KPT <= 8, "prefetch registers");
 
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[TK * KSTR];
-  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[D * VSTR];
+  // two stages of (K tile, V^T tile): a tile is written while the previous one is read
+  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][TK * KSTR];
+  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][D * VSTR];
   __shared__ int s_pmax[NWAVES];
 
   const int tid = threadIdx.x;
@@ -113,9 +116,11 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   const int n_tiles = p_bmax / TK + 1;
 
   // ---- staging roles -----------------------------------------------------------
-  // V: thread (q8, dg) owns kv rows 8*q8..+7 x d columns 8*dg..+7 of the tile.
-  const int v_dg = 8 * wave + (lane & 7);
-  const int v_q8 = lane >> 3;
+  // V: thread (q8, dg) owns kv rows 8*q8..+7 x d columns 8*dg..+7 of the tile.  q8 varies fastest
+  // over the lanes so that the eight transposed 16-byte rows a wavefront writes per
+  // instruction land in distinct LDS banks; the global loads still cover whole 128-byte lines.
+  const int v_q8 = lane & 7;
+  const int v_dg = 8 * wave + (lane >> 3);
   const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
   const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
   const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
       }
     }
   };
-  auto store_tile = [&]() {
+  auto store_tile = [&](int stage) {
     if (wave < 2) {
       // 8x8 transpose in registers: word w of output row di pairs kv rows 2w, 2w+1 at d column di
 #pragma unroll
@@ -151,13 +156,14 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
           const uint32_t b = pre[2 * w + 1][di >> 1];
           o[w] = (di & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
         }
-        *reinterpret_cast<v4u *>(&vt_lds[(8 * v_dg + di) * VSTR + 8 * v_q8]) = o;
+        *reinterpret_cast<v4u *>(&vt_lds[stage][(8 * v_dg + di) * VSTR + 8 * v_q8]) = o;
       }
     } else {
 #pragma unroll
       for (int i = 0; i < KPT; ++i) {
         const int vi = (tid - 128) + i * KTHREADS;
-        if (vi < TK * D / 8) *reinterpret_cast<v4u *>(&k_lds[(vi >> 4) * KSTR + 8 * (vi & 15)]) = pre[i];
+        // kv row j is stored at LDS row sigma(j): MFMA A-row i then reads LDS row i
+        if (vi < TK * D / 8) *reinterpret_cast<v4u *>(&k_lds[stage][sigma(vi >> 4) * KSTR + 8 * (vi & 15)]) = pre[i];
       }
     }
   };
@@ -171,16 +177,14 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   float m_run = -INFINITY;  // running max of the scaled logits, log2 domain
   float l_run = 0.f;        // this lane's share of the running sum
 
-  const int srow = sigma(col);
   issue_loads(0);
+  store_tile(0);
+  if (n_tiles > 1) issue_loads(TK);
+  __syncthreads();
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int j0 = tile * TK;
-    __syncthreads();  // everyone is done reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (tile + 1 < n_tiles) issue_loads(j0 + TK);
-    if (j0 > p_wmax) continue;  // this wavefront's rows end before the tile (it still stages and syncs)
-
+    const int cur = tile & 1;
+    if (j0 <= p_wmax) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
     f32x16 S[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
       for (int r = 0; r < 16; ++r) S[t][r] = 0.f;
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        const v4u x = *reinterpret_cast<const v4u *>(&k_lds[(32 * t + srow) * KSTR + 16 * s + 8 * hf]);
+        const v4u x = *reinterpret_cast<const v4u *>(&k_lds[cur][(32 * t + col) * KSTR + 16 * s + 8 * hf]);
         S[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), qf[s], S[t], 0, 0, 0);
       }
     }
@@ -217,16 +221,15 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
         for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
       m_run = m_new;
     }
-    float psum = 0.f;
+    float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pv = __builtin_amdgcn_exp2f(fmaf(S[t][r], scale_log2, -m_run));
-        S[t][r] = pv;
-        psum += pv;
+        S[t][r] = __builtin_amdgcn_exp2f(fmaf(S[t][r], scale_log2, -m_run));
+        psum[r & 3] += S[t][r];  // four independent chains; fp32 sum of the unrounded probabilities
       }
-    l_run += psum;
+    l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
 
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -239,10 +242,18 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
       const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) {
-        const v4u x = *reinterpret_cast<const v4u *>(&vt_lds[(32 * dt + col) * VSTR + 16 * u + 8 * hf]);
+        const v4u x = *reinterpret_cast<const v4u *>(&vt_lds[cur][(32 * dt + col) * VSTR + 16 * u + 8 * hf]);
         O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), pfrag, O[dt], 0, 0, 0);
       }
     }
+    }  // compute
+    // stage the next tile into the other buffer (last read one iteration ago, before the
+    // previous barrier) and start fetching the one after it
+    if (tile + 1 < n_tiles) {
+      store_tile(cur ^ 1);
+      if (tile + 2 < n_tiles) issue_loads(j0 + 2 * TK);
+    }
+    __syncthreads();
   }
 
   // ---- epilogue ------------------------------------------------------------------
@@ -278,11 +289,12 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
   const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
-  // 256 query columns per block halve the K/V traffic per flop; fall back to
-  // 128 when that would leave too few blocks to fill the chip.
+  // 256 query columns (8 wavefronts) per block halve the K/V traffic per flop; fall back to 128
+  // when that would leave too few blocks to fill the chip.  IFKV_ATTN_WAVES=4|8 overrides.
   const int rpb8 = 256 / G;
   const int64_t blocks8 = ((n_rows + rpb8 - 1) / rpb8) * d.n_kv_heads;
-  const bool big = blocks8 >= 512;
+  bool big = blocks8 >= 512;
+  if (const char *env = getenv("IFKV_ATTN_WAVES")) big = atoi(env) == 8;
   const int rpb = big ? rpb8 : 128 / G;
   const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
   dim3 grid(d.n_kv_heads, n_rb);
