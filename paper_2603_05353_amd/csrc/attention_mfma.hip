@@ -1,11 +1,11 @@
-// Stage 4, bf16 MFMA kernel -- "KV Recomputation": each selected row attends
+// Stage 4, bf16 MFMA kernels -- "KV Recomputation": each selected row attends
 // causally to cache rows 0..p_r of the concatenated sequence.
 //
 // Shape of the problem: few, scattered query rows (k = rho N of them) against a
-// long, dense K/V prefix.  The kernel therefore packs the G query heads that
+// long, dense K/V prefix.  The kernels therefore pack the G query heads that
 // share a kv head together with a block of consecutive selected rows into one
 // tile of NWAVES*32 "query columns", so that every K/V tile fetched from HBM/L2
-// is used by all of them, and walks the kv axis in tiles of 64 rows with an
+// is used by all of them, and walk the kv axis in tiles of 64 rows with an
 // online softmax (flash-attention style).  Rows are sorted by position, so only
 // the last one or two kv tiles of a wavefront need the causal mask.
 //
@@ -18,8 +18,16 @@
 // exchange per tile, and the S^T accumulator layout is exactly the B-operand
 // layout of the second product once the K rows are fed in a fixed permuted
 // order (sigma below): no LDS round trip for P.
-// V is transposed on its way into LDS (8x8 register transposes) because the
-// second product contracts over kv, which is the strided axis of the cache.
+// Staging uses the gfx950 direct global->LDS loads (16 bytes per lane, no registers, no VALU) and
+// keeps NS tiles in an LDS ring.  K rows land in sigma order with their 16-byte chunks XOR-swizzled
+// by the row index, so the A-operand reads (32 rows, one chunk) hit distinct banks.  V lands
+// row-major, swizzled by the row within each group of four rows, and the A operand of the second
+// product -- which needs eight kv values of one d column per lane, the strided axis -- is read
+// with the LDS transpose loads (ds_read_b64_tr_b16), two per operand.
+//
+// attn_mfma_kernel<8, 3>: 256 query columns per block, three LDS stages (96 KiB, one block per CU).
+// attn_mfma_kernel<4, 2>: 128 query columns, two stages (64 KiB, two blocks per CU); used when there
+// are too few rows for 256-column blocks to fill the chip.
 #include <cstdlib>
 
 #include "attention_common.h"
@@ -33,11 +41,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int D = 128;        // head_dim served by this kernel
+constexpr int D = 128;        // head_dim served by these kernels
 constexpr int TK = 64;        // kv rows per tile
-constexpr int KSTR = D + 8;   // LDS row stride of the K tile in elements (272 B: conflict-free b128 reads)
-constexpr int VSTR = TK + 8;  // LDS row stride of the V^T tile in elements (144 B)
+constexpr int TILE_ELEMS = TK * D;  // one K or V tile in LDS: 64 rows x 256 B, no padding (swizzled instead)
+// The running max is only raised (and O, l rescaled) when a new tile exceeds it by more than
+// this many powers of two, so probabilities stay <= 2^kSlack: exact in fp32 sums and harmless
+// for the bf16 rounding, and the 64-register rescale becomes rare.
+constexpr float kSlack = 8.f;
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   f32x2 v = {a, b};
@@ -46,233 +59,320 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 // Order in which K rows are fed as MFMA A-rows.  A 32x32 accumulator gives lane
-// half hf, register r the A-row 8*(r/4) + 4*hf + r%4; feeding row sigma(i) as
+// half hf, register r the A-row 8*(r/4) + 4*hf + r%4; feeding kv row sigma(i) as
 // A-row i makes registers 0..7 of a lane hold kv rows 8*hf + 0..7 and registers
 // 8..15 hold kv rows 16 + 8*hf + 0..7, i.e. eight consecutive kv rows per
 // 16-row contraction step, which is what the B operand of V^T.P^T needs.
+// sigma swaps bits 2 and 3 (an involution); K rows are stored in LDS at row
+// sigma(j), so A-row i simply reads LDS row i.
 __device__ __forceinline__ int sigma(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
-template <int NWAVES>
-__global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
-    const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ row_pos, int n_rows,
-    const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache, int n_kv,
-    uint16_t *__restrict__ out, float *__restrict__ lse_out, int n_q_heads, int n_kv_heads,
-    float scale_log2, int rows_per_block) {
-  constexpr int NT = NWAVES * 64;
-  constexpr int KTHREADS = NT - 128;                         // threads that stage K (the first 128 stage V)
-  constexpr int KPT = (TK * D / 8 + KTHREADS - 1) / KTHREADS;  // 16-byte K vectors per staging thread
-  static_assert(KPT <= 8, "prefetch registers");
+// Everything one wavefront carries through the kv loop.
+struct WaveState {
+  f32x16 O[4];   // O^T accumulator, 128 d x 32 q
+  float m_run;   // reference max of the scaled logits (log2 domain); may lag the true max by <= kSlack
+  float l_run;   // this lane's share of the running sum
+};
 
-  // two stages of (K tile, V^T tile): a tile is written while the previous one is read
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][TK * KSTR];
-  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][D * VSTR];
-  __shared__ int s_pmax[NWAVES];
+// Per-lane LDS read offsets (in elements) that do not change from tile to tile.
+struct ReadOffsets {
+  int k[8];  // K A-operand, contraction step s: row (lane & 31), chunk (2 s + hf) ^ (row & 15)
+  int v[4];  // V transpose read, d tile dt (see pv_tile)
+};
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int col = lane & 31;
-  const int hf = lane >> 5;
-  const int G = n_q_heads / n_kv_heads;
-  const int g = blockIdx.x;
-  const int rb = gridDim.y - 1 - blockIdx.y;  // longest prefixes are dispatched first
-  const int row0 = rb * rows_per_block;
+__device__ __forceinline__ ReadOffsets make_read_offsets(int lane) {
+  ReadOffsets o;
+  const int col = lane & 31, hf = lane >> 5;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) o.k[s] = col * D + (((2 * s + hf) ^ (col & 15)) << 3);
+  // transpose read: in every group of 16 lanes, lane j supplies row j / 4, d columns 4 (j % 4)..+3
+  // (8 bytes) and receives the four rows of d column j.  Group g covers d columns 16 (g & 1)..+15
+  // of the 32-column d tile; hf = g / 2 selects kv rows +8.
+  const int g = lane >> 4, j = lane & 15;
+  const int r = j >> 2;
+  const int low = 2 * (g & 1) + ((j & 3) >> 1);  // 16-byte chunk within the d tile's four chunks
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+    o.v[dt] = (2 * hf) * 512 + ((16 * r + ((4 * dt + low) ^ (4 * r))) << 3) + 4 * (j & 1);
+  return o;
+}
 
-  // ---- this lane's query column -------------------------------------------------
-  const int qc = wave * 32 + col;
-  const int rr = qc / G;
-  const int hh = qc - rr * G;
-  const int row = row0 + rr;
-  const bool col_valid = (rr < rows_per_block) && (row < n_rows);
-  int p_q = 0;
-  bool in_range = false;
-  if (col_valid) {
-    const int p = row_pos[row];
-    in_range = (p >= 0) && (p < n_kv);
-    p_q = in_range ? p : 0;
+// S^T = K_tile . Q^T for one 64-row tile held in LDS stage `k_stage`.
+__device__ __forceinline__ void qk_tile(f32x16 (&S)[2], const uint16_t *k_stage, const bf16x8 (&qf)[8],
+                                        const ReadOffsets &ro) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    S[0][r] = 0.f;
+    S[1][r] = 0.f;
   }
-  const int64_t q_off = (static_cast<int64_t>(row) * n_q_heads + g * G + hh) * D;
-
-  bf16x8 qf[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    v4u x = {0u, 0u, 0u, 0u};
-    if (col_valid) x = *reinterpret_cast<const v4u *>(q_sel + q_off + 16 * s + 8 * hf);
-    qf[s] = __builtin_bit_cast(bf16x8, x);
+    const v4u ka = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s]]);
+    const v4u kb = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s] + 32 * D]);
+    S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), qf[s], S[0], 0, 0, 0);
+    S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb), qf[s], S[1], 0, 0, 0);
   }
+}
 
-  // wavefront and block extents of the causal prefix
-  int p_wmax = p_q, p_wmin = col_valid ? p_q : 0x7FFFFFFF;
+// Causal mask (only on tiles that reach past the wavefront's smallest position), row max, and
+// the lazy update of the reference max with the rescale of O and l it implies.
+// Register r of S[t] is kv row j0 + 32 t + 16 (r / 8) + 8 hf + r % 8.
+__device__ __forceinline__ void row_stats(f32x16 (&S)[2], WaveState &w, int j0, int p_q, int p_wmin, int hf,
+                                          float scale_log2) {
+  if (j0 + TK - 1 > p_wmin) {
+    const int base = j0 + 8 * hf - p_q;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (base + 32 * t + 16 * (r >> 3) + (r & 7) > 0) S[t][r] = -INFINITY;
+  }
+  float mx = S[0][0];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[t][r]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(w.m_run, mx * scale_log2);
+  if (__any(m_new > w.m_run + kSlack)) {
+    const float alpha = __builtin_amdgcn_exp2f(w.m_run - m_new);  // 0 on the first tile (m_run = -inf)
+    w.l_run *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) w.O[dt][r] *= alpha;
+    w.m_run = m_new;
+  }
+}
+
+// P^T of one tile, rounded to bf16 and packed as the four B operands of the second product.
+struct PTile {
+  v4u step[4];  // contraction step u: kv rows 16 u + 8 hf + 0..7 of this lane's query column
+};
+
+// P^T = exp2(S^T c - m) and l += sum P (fp32, before rounding).
+__device__ __forceinline__ void exp_tile(f32x16 (&S)[2], WaveState &w, PTile &P, float scale_log2) {
+  float psum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      S[t][r] = __builtin_amdgcn_exp2f(fmaf(S[t][r], scale_log2, -w.m_run));
+      psum[r & 3] += S[t][r];
+    }
+  w.l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int t = u >> 1, r0 = 8 * (u & 1);
+    P.step[u][0] = pack_bf16x2(S[t][r0 + 0], S[t][r0 + 1]);
+    P.step[u][1] = pack_bf16x2(S[t][r0 + 2], S[t][r0 + 3]);
+    P.step[u][2] = pack_bf16x2(S[t][r0 + 4], S[t][r0 + 5]);
+    P.step[u][3] = pack_bf16x2(S[t][r0 + 6], S[t][r0 + 7]);
+  }
+}
+
+// O^T += V_tile^T . P^T.  The A operand of contraction step u, d tile dt is lane (d = 32 dt + lane % 32)
+// x kv rows 16 u + 8 hf + 0..7: two transpose reads of four rows each from the row-major V tile.
+__device__ __forceinline__ void pv_tile(const PTile &P, WaveState &w, const uint16_t *v_stage, const ReadOffsets &ro) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const bf16x8 pfrag = __builtin_bit_cast(bf16x8, P.step[u]);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const uint16_t *p = v_stage + ro.v[dt] + (4 * u) * 512;  // 4-row groups 4 u + 2 hf (+1)
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 512));
+      const s16x8 x = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      w.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), pfrag, w.O[dt], 0, 0, 0);
+    }
+  }
+}
+
+// Direct global->LDS staging of one kv tile.  A load instruction moves 64 x 16 bytes: lane L's
+// 16 bytes land at the instruction's LDS base + 16 L, whatever global address the lane names, so
+// a "unit" of 1 KiB = four 256-byte tile rows is filled per instruction and the lanes choose which
+// chunk goes where.  K unit q: LDS rows 4q..4q+3 hold kv rows sigma(4q..4q+3); position c of a row
+// holds chunk c ^ (row & 15).  V unit q: kv rows 4q..4q+3; position c of row r holds chunk c ^ 4r.
+//
+// The load is emitted as inline assembly (M0 = LDS base of the instruction, then the load).  The
+// compiler's own builtin works, but it cannot tell which LDS stage such a load writes and so
+// waits for ALL outstanding loads before every later LDS read, which serialises the look-ahead.
+// Ordering is done by hand instead: a vmcnt wait plus a barrier before a stage is read.
+__device__ __forceinline__ void dma16(const void *global_src, const void *lds_dst) {
+  const uint32_t la = static_cast<uint32_t>(
+      reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void *)lds_dst));
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(global_src), "s"(__builtin_amdgcn_readfirstlane(la))
+               : "memory");
+}
+
+template <int NWAVES>
+struct Dma {
+  static constexpr int UPW = 16 / NWAVES;   // units per wavefront and matrix (2 or 4)
+  static constexpr int PER_TILE = 2 * UPW;  // load instructions a wavefront issues per tile
+};
+
+template <int NWAVES>
+__device__ __forceinline__ void issue_tile_dma(uint16_t *k_stage, uint16_t *v_stage, const uint16_t *k_base,
+                                               const uint16_t *v_base, int64_t kv_row_elems, int j0, int n_kv) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane >> 4, cpos = lane & 15;
+#pragma unroll
+  for (int x = 0; x < Dma<NWAVES>::UPW; ++x) {
+    const int unit = wave * Dma<NWAVES>::UPW + x;
+    const int i = 4 * unit + r;  // LDS row
+    const int jk = min(j0 + sigma(i), n_kv - 1);
+    const int jv = min(j0 + i, n_kv - 1);
+    const uint16_t *gk = k_base + jk * kv_row_elems + 8 * (cpos ^ (i & 15));
+    const uint16_t *gv = v_base + jv * kv_row_elems + 8 * (cpos ^ (4 * r));
+    dma16(gk, k_stage + unit * 512);
+    dma16(gv, v_stage + unit * 512);
+  }
+}
+
+// Per-lane query column set-up shared by both kernels.
+struct Column {
+  int row, hh, p_q, p_wmax, p_wmin;
+  bool col_valid, in_range;
+  int64_t q_off;
+};
+
+__device__ __forceinline__ Column setup_column(const int32_t *__restrict__ row_pos, int n_rows, int n_kv, int row0,
+                                               int rows_per_block, int G, int g, int n_q_heads) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  Column c;
+  const int qc = wave * 32 + (lane & 31);
+  const int rr = qc / G;
+  c.hh = qc - rr * G;
+  c.row = row0 + rr;
+  c.col_valid = (rr < rows_per_block) && (c.row < n_rows);
+  // Loads are unconditional on a clamped row (then zeroed): no divergent control flow before
+  // the main loop, so no memory operation is still pending on a side path when it is entered.
+  const int row_c = min(c.row, n_rows - 1);
+  const int p_ld = row_pos[row_c];
+  c.in_range = c.col_valid && (p_ld >= 0) && (p_ld < n_kv);
+  c.p_q = c.in_range ? p_ld : 0;
+  c.q_off = (static_cast<int64_t>(row_c) * n_q_heads + g * G + c.hh) * D;
+  int p_wmax = c.p_q, p_wmin = c.col_valid ? c.p_q : 0x7FFFFFFF;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     p_wmax = max(p_wmax, __shfl_xor(p_wmax, o, 64));
     p_wmin = min(p_wmin, __shfl_xor(p_wmin, o, 64));
   }
+  c.p_wmax = __builtin_amdgcn_readfirstlane(p_wmax);
+  c.p_wmin = __builtin_amdgcn_readfirstlane(p_wmin);
+  return c;
+}
+
+__device__ __forceinline__ void load_q_frags(bf16x8 (&qf)[8], const uint16_t *__restrict__ q_sel, const Column &c,
+                                             int hf) {
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    v4u x = *reinterpret_cast<const v4u *>(q_sel + c.q_off + 16 * s + 8 * hf);
+    if (!c.col_valid) x = v4u{0u, 0u, 0u, 0u};
+    qf[s] = __builtin_bit_cast(bf16x8, x);
+  }
+}
+
+__device__ __forceinline__ void write_output(const WaveState &w, const Column &c, uint16_t *__restrict__ out,
+                                             float *__restrict__ lse_out, int n_q_heads, int g, int G, int hf) {
+  if (!c.col_valid) return;
+  const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
+  const float inv = c.in_range ? 1.f / l_tot : 0.f;
+  uint16_t *orow = out + c.q_off;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int ri = 0; ri < 4; ++ri) {
+      uint2 x;
+      x.x = pack_bf16x2(w.O[dt][4 * ri + 0] * inv, w.O[dt][4 * ri + 1] * inv);
+      x.y = pack_bf16x2(w.O[dt][4 * ri + 2] * inv, w.O[dt][4 * ri + 3] * inv);
+      *reinterpret_cast<uint2 *>(orow + 32 * dt + 8 * ri + 4 * hf) = x;
+    }
+  if (lse_out != nullptr && hf == 0)
+    lse_out[static_cast<int64_t>(c.row) * n_q_heads + g * G + c.hh] =
+        c.in_range ? 0.6931471805599453f * (w.m_run + __log2f(l_tot)) : 0.f;
+}
+
+template <int NWAVES>
+__device__ __forceinline__ int block_tiles(int p_wmax, int *s_pmax) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) s_pmax[wave] = p_wmax;
   __syncthreads();
   int p_bmax = 0;
 #pragma unroll
   for (int w = 0; w < NWAVES; ++w) p_bmax = max(p_bmax, s_pmax[w]);
-  const int n_tiles = p_bmax / TK + 1;
+  return p_bmax / TK + 1;
+}
 
-  // ---- staging roles -----------------------------------------------------------
-  // V: thread (q8, dg) owns kv rows 8*q8..+7 x d columns 8*dg..+7 of the tile.  q8 varies fastest
-  // over the lanes so that the eight transposed 16-byte rows a wavefront writes per
-  // instruction land in distinct LDS banks; the global loads still cover whole 128-byte lines.
-  const int v_q8 = lane & 7;
-  const int v_dg = 8 * wave + (lane >> 3);
+// ---------------------------------------------------------------------------
+// NWAVES wavefronts, ring of NS LDS stages filled by direct global->LDS loads NS-1 tiles ahead.
+// ---------------------------------------------------------------------------
+template <int NWAVES, int NS>
+__global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
+    const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ row_pos, int n_rows,
+    const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache, int n_kv,
+    uint16_t *__restrict__ out, float *__restrict__ lse_out, int n_q_heads, int n_kv_heads, float scale_log2,
+    int rows_per_block) {
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds[NS][TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds[NS][TILE_ELEMS];
+  __shared__ int s_pmax[NWAVES];
+
+  const int lane = threadIdx.x & 63;
+  const int hf = lane >> 5;
+  const int G = n_q_heads / n_kv_heads;
+  const int g = blockIdx.x;
+  const int rb = gridDim.y - 1 - blockIdx.y;  // longest prefixes are dispatched first
+  const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads);
+  bf16x8 qf[8];
+  load_q_frags(qf, q_sel, c, hf);
+  const int n_tiles = block_tiles<NWAVES>(c.p_wmax, s_pmax);
+  const ReadOffsets ro = make_read_offsets(lane);
+
   const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
   const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
   const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
 
-  v4u pre[8];
-  auto issue_loads = [&](int j0) {
-    if (wave < 2) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int jr = min(j0 + 8 * v_q8 + i, n_kv - 1);
-        pre[i] = *reinterpret_cast<const v4u *>(v_base + jr * kv_row_elems + 8 * v_dg);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < KPT; ++i) {
-        const int vi = (tid - 128) + i * KTHREADS;
-        if (vi < TK * D / 8) {
-          const int jr = min(j0 + (vi >> 4), n_kv - 1);
-          pre[i] = *reinterpret_cast<const v4u *>(k_base + jr * kv_row_elems + 8 * (vi & 15));
-        }
-      }
-    }
-  };
-  auto store_tile = [&](int stage) {
-    if (wave < 2) {
-      // 8x8 transpose in registers: word w of output row di pairs kv rows 2w, 2w+1 at d column di
-#pragma unroll
-      for (int di = 0; di < 8; ++di) {
-        v4u o;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const uint32_t a = pre[2 * w][di >> 1];
-          const uint32_t b = pre[2 * w + 1][di >> 1];
-          o[w] = (di & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
-        }
-        *reinterpret_cast<v4u *>(&vt_lds[stage][(8 * v_dg + di) * VSTR + 8 * v_q8]) = o;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < KPT; ++i) {
-        const int vi = (tid - 128) + i * KTHREADS;
-        // kv row j is stored at LDS row sigma(j): MFMA A-row i then reads LDS row i
-        if (vi < TK * D / 8) *reinterpret_cast<v4u *>(&k_lds[stage][sigma(vi >> 4) * KSTR + 8 * (vi & 15)]) = pre[i];
-      }
-    }
-  };
-
-  // ---- main loop ---------------------------------------------------------------
-  f32x16 O[4];
+  WaveState w;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
-  float m_run = -INFINITY;  // running max of the scaled logits, log2 domain
-  float l_run = 0.f;        // this lane's share of the running sum
+    for (int r = 0; r < 16; ++r) w.O[dt][r] = 0.f;
+  w.m_run = -INFINITY;
+  w.l_run = 0.f;
 
-  issue_loads(0);
-  store_tile(0);
-  if (n_tiles > 1) issue_loads(TK);
-  __syncthreads();
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int j0 = tile * TK;
-    const int cur = tile & 1;
-    if (j0 <= p_wmax) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
-    f32x16 S[2];
+  // Tiles 0 .. NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
+  // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) S[t][r] = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const v4u x = *reinterpret_cast<const v4u *>(&k_lds[cur][(32 * t + col) * KSTR + 16 * s + 8 * hf]);
-        S[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), qf[s], S[t], 0, 0, 0);
-      }
-    }
-    // register r of S[t] is kv row j0 + 32 t + 16 (r / 8) + 8 hf + r % 8
-    if (j0 + TK - 1 > p_wmin) {
-      const int base = j0 + 8 * hf - p_q;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (base + 32 * t + 16 * (r >> 3) + (r & 7) > 0) S[t][r] = -INFINITY;
-    }
-    float mx = S[0][0];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[t][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * scale_log2);
-    if (__any(m_new > m_run)) {
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-      m_run = m_new;
-    }
-    float psum[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        S[t][r] = __builtin_amdgcn_exp2f(fmaf(S[t][r], scale_log2, -m_run));
-        psum[r & 3] += S[t][r];  // four independent chains; fp32 sum of the unrounded probabilities
-      }
-    l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
+  for (int t = 0; t < NS - 1; ++t)
+    issue_tile_dma<NWAVES>(k_lds[t], v_lds[t], k_base, v_base, kv_row_elems, t * TK, n_kv);
 
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int t = u >> 1, r0 = 8 * (u & 1);
-      v4u pb;
-      pb[0] = pack_bf16x2(S[t][r0 + 0], S[t][r0 + 1]);
-      pb[1] = pack_bf16x2(S[t][r0 + 2], S[t][r0 + 3]);
-      pb[2] = pack_bf16x2(S[t][r0 + 4], S[t][r0 + 5]);
-      pb[3] = pack_bf16x2(S[t][r0 + 6], S[t][r0 + 7]);
-      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        const v4u x = *reinterpret_cast<const v4u *>(&vt_lds[cur][(32 * dt + col) * VSTR + 16 * u + 8 * hf]);
-        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), pfrag, O[dt], 0, 0, 0);
-      }
+  const int my_tiles = min(n_tiles, c.p_wmax / TK + 1);
+  int st = 0;  // ring position of tile i
+  for (int i = 0; i < n_tiles; ++i) {
+    // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
+    // (loads complete in order; the query loads issued before them are therefore complete too)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
+    __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
+    {
+      const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
+      issue_tile_dma<NWAVES>(k_lds[wr], v_lds[wr], k_base, v_base, kv_row_elems, (i + NS - 1) * TK, n_kv);
     }
-    }  // compute
-    // stage the next tile into the other buffer (last read one iteration ago, before the
-    // previous barrier) and start fetching the one after it
-    if (tile + 1 < n_tiles) {
-      store_tile(cur ^ 1);
-      if (tile + 2 < n_tiles) issue_loads(j0 + 2 * TK);
+    if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
+      f32x16 S[2];
+      qk_tile(S, k_lds[st], qf, ro);
+      row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
+      PTile P;
+      exp_tile(S, w, P, scale_log2);
+      pv_tile(P, w, v_lds[st], ro);
     }
-    __syncthreads();
+    st = (st == NS - 1) ? 0 : st + 1;
   }
-
-  // ---- epilogue ------------------------------------------------------------------
-  if (!col_valid) return;
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = in_range ? 1.f / l_tot : 0.f;
-  uint16_t *orow = out + q_off;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int ri = 0; ri < 4; ++ri) {
-      uint2 w;
-      w.x = pack_bf16x2(O[dt][4 * ri + 0] * inv, O[dt][4 * ri + 1] * inv);
-      w.y = pack_bf16x2(O[dt][4 * ri + 2] * inv, O[dt][4 * ri + 3] * inv);
-      *reinterpret_cast<uint2 *>(orow + 32 * dt + 8 * ri + 4 * hf) = w;
-    }
-  if (lse_out != nullptr && hf == 0)
-    lse_out[static_cast<int64_t>(row) * n_q_heads + g * G + hh] =
-        in_range ? 0.6931471805599453f * (m_run + __log2f(l_tot)) : 0.f;
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is released
+  write_output(w, c, out, lse_out, n_q_heads, g, G, hf);
 }
 
 }  // namespace
@@ -299,17 +399,15 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
   const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
   dim3 grid(d.n_kv_heads, n_rb);
   if (big) {
-    hipLaunchKernelGGL((attn_mfma_kernel<8>), grid, dim3(512), 0, ctx->stream,
-                       static_cast<const uint16_t *>(q_sel), row_pos, static_cast<int>(n_rows),
-                       static_cast<const uint16_t *>(k_cache), static_cast<const uint16_t *>(v_cache),
-                       static_cast<int>(n_kv), static_cast<uint16_t *>(out), lse_out, d.n_q_heads, d.n_kv_heads,
-                       scale_log2, rpb);
+    hipLaunchKernelGGL((attn_mfma_kernel<8, 3>), grid, dim3(512), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
+                       row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
+                       static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
+                       lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb);
   } else {
-    hipLaunchKernelGGL((attn_mfma_kernel<4>), grid, dim3(256), 0, ctx->stream,
-                       static_cast<const uint16_t *>(q_sel), row_pos, static_cast<int>(n_rows),
-                       static_cast<const uint16_t *>(k_cache), static_cast<const uint16_t *>(v_cache),
-                       static_cast<int>(n_kv), static_cast<uint16_t *>(out), lse_out, d.n_q_heads, d.n_kv_heads,
-                       scale_log2, rpb);
+    hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
+                       row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
+                       static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
+                       lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb);
   }
   return hipGetLastError();
 }
