@@ -25,9 +25,10 @@
 // product -- which needs eight kv values of one d column per lane, the strided axis -- is read
 // with the LDS transpose loads (ds_read_b64_tr_b16), two per operand.
 //
-// attn_mfma_kernel<8, 3>: 256 query columns per block, three LDS stages (96 KiB, one block per CU).
-// attn_mfma_kernel<4, 2>: 128 query columns, two stages (64 KiB, two blocks per CU); used when there
-// are too few rows for 256-column blocks to fill the chip.
+// attn_mfma_kernel<4, 2>: 128 query columns per block, two LDS stages (64 KiB), two blocks per CU --
+// the default.  The two wavefronts that share a SIMD then belong to different blocks and are not
+// tied together by barriers.  attn_mfma_kernel<8, 3>: 256 query columns, three stages (96 KiB), one
+// block per CU; half the K/V traffic per flop, measured within 2 % of the default.
 #include <cstdlib>
 
 #include "attention_common.h"
@@ -67,6 +68,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // sigma(j), so A-row i simply reads LDS row i.
 __device__ __forceinline__ int sigma(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
+// max of a value with the one held by the lane 32 positions away (the other half of the same
+// query column): one lane-half swap in the vector ALU instead of a round trip through LDS.
+__device__ __forceinline__ float half_swap_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // Everything one wavefront carries through the kv loop.
 struct WaveState {
   f32x16 O[4];   // O^T accumulator, 128 d x 32 q
@@ -97,20 +105,33 @@ __device__ __forceinline__ ReadOffsets make_read_offsets(int lane) {
   return o;
 }
 
-// S^T = K_tile . Q^T for one 64-row tile held in LDS stage `k_stage`.
+// S^T = K_tile . Q^T for one 64-row tile held in LDS stage `k_stage`.  An MFMA takes 32 cycles, an
+// LDS read returns after a few hundred when eight wavefronts share the LDS, so the A operands are
+// requested four contraction steps (eight reads) ahead of their use; the fences keep the
+// compiler from sinking the reads back next to their consumers.
 __device__ __forceinline__ void qk_tile(f32x16 (&S)[2], const uint16_t *k_stage, const bf16x8 (&qf)[8],
                                         const ReadOffsets &ro) {
+  v4u ka[8], kb[8];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    ka[s] = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s]]);
+    kb[s] = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s] + 32 * D]);
+  }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     S[0][r] = 0.f;
     S[1][r] = 0.f;
   }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    const v4u ka = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s]]);
-    const v4u kb = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s] + 32 * D]);
-    S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), qf[s], S[0], 0, 0, 0);
-    S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb), qf[s], S[1], 0, 0, 0);
+    S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[s]), qf[s], S[0], 0, 0, 0);
+    S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb[s]), qf[s], S[1], 0, 0, 0);
+    if (s + 4 < 8) {
+      ka[s + 4] = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s + 4]]);
+      kb[s + 4] = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s + 4] + 32 * D]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -132,7 +153,7 @@ __device__ __forceinline__ void row_stats(f32x16 (&S)[2], WaveState &w, int j0, 
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[t][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  mx = half_swap_max(mx);
   const float m_new = fmaxf(w.m_run, mx * scale_log2);
   if (__any(m_new > w.m_run + kSlack)) {
     const float alpha = __builtin_amdgcn_exp2f(w.m_run - m_new);  // 0 on the first tile (m_run = -inf)
@@ -173,19 +194,33 @@ __device__ __forceinline__ void exp_tile(f32x16 (&S)[2], WaveState &w, PTile &P,
 
 // O^T += V_tile^T . P^T.  The A operand of contraction step u, d tile dt is lane (d = 32 dt + lane % 32)
 // x kv rows 16 u + 8 hf + 0..7: two transpose reads of four rows each from the row-major V tile.
-__device__ __forceinline__ void pv_tile(const PTile &P, WaveState &w, const uint16_t *v_stage, const ReadOffsets &ro) {
+// The sixteen operands are numbered x = 4 u + dt and requested four ahead; the first four are
+// requested by pv_preload, which the caller places before the exponentials (they do not depend on
+// them), so that they arrive while the vector ALU is busy.
+struct VFrags {
+  s16x4 lo[4], hi[4];
+};
+__device__ __forceinline__ void v_read(s16x4 &lo, s16x4 &hi, const uint16_t *v_stage, const ReadOffsets &ro, int x) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const uint16_t *p = v_stage + ro.v[x & 3] + (4 * (x >> 2)) * 512;  // 4-row groups 4 u + 2 hf (+1)
+  lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+  hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 512));
+}
+__device__ __forceinline__ void pv_preload(VFrags &f, const uint16_t *v_stage, const ReadOffsets &ro) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const bf16x8 pfrag = __builtin_bit_cast(bf16x8, P.step[u]);
+  for (int x = 0; x < 4; ++x) v_read(f.lo[x], f.hi[x], v_stage, ro, x);
+}
+__device__ __forceinline__ void pv_tile(const PTile &P, VFrags &f, WaveState &w, const uint16_t *v_stage,
+                                        const ReadOffsets &ro) {
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const uint16_t *p = v_stage + ro.v[dt] + (4 * u) * 512;  // 4-row groups 4 u + 2 hf (+1)
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 512));
-      const s16x8 x = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      w.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), pfrag, w.O[dt], 0, 0, 0);
-    }
+  for (int x = 0; x < 16; ++x) {
+    const int u = x >> 2, dt = x & 3;
+    const s16x8 a = __builtin_shufflevector(f.lo[x & 3], f.hi[x & 3], 0, 1, 2, 3, 4, 5, 6, 7);
+    w.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                      __builtin_bit_cast(bf16x8, P.step[u]), w.O[dt], 0, 0, 0);
+    if (x + 4 < 16) v_read(f.lo[x & 3], f.hi[x & 3], v_stage, ro, x + 4);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -199,12 +234,21 @@ __device__ __forceinline__ void pv_tile(const PTile &P, WaveState &w, const uint
 // compiler's own builtin works, but it cannot tell which LDS stage such a load writes and so
 // waits for ALL outstanding loads before every later LDS read, which serialises the look-ahead.
 // Ordering is done by hand instead: a vmcnt wait plus a barrier before a stage is read.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void *)p));
+}
+// per-lane 64-bit global address
 __device__ __forceinline__ void dma16(const void *global_src, const void *lds_dst) {
-  const uint32_t la = static_cast<uint32_t>(
-      reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void *)lds_dst));
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
                :
-               : "v"(global_src), "s"(__builtin_amdgcn_readfirstlane(la))
+               : "v"(global_src), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds_dst)))
+               : "memory");
+}
+// wavefront-uniform 64-bit base + per-lane 32-bit byte offset
+__device__ __forceinline__ void dma16_base(const void *uniform_base, uint32_t lane_offset, const void *lds_dst) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_offset), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds_dst)))
                : "memory");
 }
 
@@ -214,22 +258,60 @@ struct Dma {
   static constexpr int PER_TILE = 2 * UPW;  // load instructions a wavefront issues per tile
 };
 
+// What a lane fetches for each of its units, as byte offsets from the tile's first row: fixed for
+// the whole kernel, so a tile that lies fully inside the cache costs one scalar base update and
+// PER_TILE load instructions, no vector arithmetic.
 template <int NWAVES>
-__device__ __forceinline__ void issue_tile_dma(uint16_t *k_stage, uint16_t *v_stage, const uint16_t *k_base,
-                                               const uint16_t *v_base, int64_t kv_row_elems, int j0, int n_kv) {
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+struct DmaPlan {
+  uint32_t k_off[Dma<NWAVES>::UPW];
+  uint32_t v_off[Dma<NWAVES>::UPW];
+};
+
+template <int NWAVES>
+__device__ __forceinline__ DmaPlan<NWAVES> make_dma_plan(int64_t kv_row_elems) {
+  DmaPlan<NWAVES> pl;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane >> 4, cpos = lane & 15;
+  const uint32_t row_bytes = static_cast<uint32_t>(kv_row_elems) * 2u;
 #pragma unroll
   for (int x = 0; x < Dma<NWAVES>::UPW; ++x) {
-    const int unit = wave * Dma<NWAVES>::UPW + x;
-    const int i = 4 * unit + r;  // LDS row
-    const int jk = min(j0 + sigma(i), n_kv - 1);
-    const int jv = min(j0 + i, n_kv - 1);
-    const uint16_t *gk = k_base + jk * kv_row_elems + 8 * (cpos ^ (i & 15));
-    const uint16_t *gv = v_base + jv * kv_row_elems + 8 * (cpos ^ (4 * r));
-    dma16(gk, k_stage + unit * 512);
-    dma16(gv, v_stage + unit * 512);
+    const int i = 4 * (wave * Dma<NWAVES>::UPW + x) + r;  // LDS row
+    pl.k_off[x] = sigma(i) * row_bytes + 16u * (cpos ^ (i & 15));
+    pl.v_off[x] = i * row_bytes + 16u * (cpos ^ (4 * r));
+  }
+  return pl;
+}
+
+template <int NWAVES>
+__device__ __forceinline__ void issue_tile_dma(const DmaPlan<NWAVES> &pl, uint16_t *k_stage, uint16_t *v_stage,
+                                               const uint16_t *k_base, const uint16_t *v_base, int64_t kv_row_elems,
+                                               int tile, int n_kv) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int j0 = tile * TK;
+  const bool partial = (j0 < n_kv && j0 + TK > n_kv) || n_kv < TK;
+  if (!partial) {
+    if (j0 >= n_kv) j0 = 0;  // look-ahead past the end: fetch any valid tile, it is never read
+    const uint16_t *kb = k_base + j0 * kv_row_elems;
+    const uint16_t *vb = v_base + j0 * kv_row_elems;
+#pragma unroll
+    for (int x = 0; x < Dma<NWAVES>::UPW; ++x) {
+      const int unit = wave * Dma<NWAVES>::UPW + x;
+      dma16_base(kb, pl.k_off[x], k_stage + unit * 512);
+      dma16_base(vb, pl.v_off[x], v_stage + unit * 512);
+    }
+  } else {
+    // the one tile that straddles the end of the cache: rows past the end are clamped (and masked later)
+    const int lane = threadIdx.x & 63;
+    const int r = lane >> 4, cpos = lane & 15;
+#pragma unroll
+    for (int x = 0; x < Dma<NWAVES>::UPW; ++x) {
+      const int unit = wave * Dma<NWAVES>::UPW + x;
+      const int i = 4 * unit + r;
+      const int jk = min(j0 + sigma(i), n_kv - 1);
+      const int jv = min(j0 + i, n_kv - 1);
+      dma16(k_base + jk * kv_row_elems + 8 * (cpos ^ (i & 15)), k_stage + unit * 512);
+      dma16(v_base + jv * kv_row_elems + 8 * (cpos ^ (4 * r)), v_stage + unit * 512);
+    }
   }
 }
 
@@ -335,6 +417,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
   const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
   const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
+  const auto plan = make_dma_plan<NWAVES>(kv_row_elems);
 
   WaveState w;
 #pragma unroll
@@ -348,7 +431,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
-    issue_tile_dma<NWAVES>(k_lds[t], v_lds[t], k_base, v_base, kv_row_elems, t * TK, n_kv);
+    issue_tile_dma<NWAVES>(plan, k_lds[t], v_lds[t], k_base, v_base, kv_row_elems, t, n_kv);
 
   const int my_tiles = min(n_tiles, c.p_wmax / TK + 1);
   int st = 0;  // ring position of tile i
@@ -359,15 +442,17 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
     {
       const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
-      issue_tile_dma<NWAVES>(k_lds[wr], v_lds[wr], k_base, v_base, kv_row_elems, (i + NS - 1) * TK, n_kv);
+      issue_tile_dma<NWAVES>(plan, k_lds[wr], v_lds[wr], k_base, v_base, kv_row_elems, i + NS - 1, n_kv);
     }
     if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
       f32x16 S[2];
       qk_tile(S, k_lds[st], qf, ro);
+      VFrags vf;
+      pv_preload(vf, v_lds[st], ro);
       row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
       PTile P;
       exp_tile(S, w, P, scale_log2);
-      pv_tile(P, w, v_lds[st], ro);
+      pv_tile(P, vf, w, v_lds[st], ro);
     }
     st = (st == NS - 1) ? 0 : st + 1;
   }
@@ -389,11 +474,9 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
   const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
-  // 256 query columns (8 wavefronts) per block halve the K/V traffic per flop; fall back to 128
-  // when that would leave too few blocks to fill the chip.  IFKV_ATTN_WAVES=4|8 overrides.
+  // IFKV_ATTN_WAVES=8 selects the 256-column variant (tuning aid).
   const int rpb8 = 256 / G;
-  const int64_t blocks8 = ((n_rows + rpb8 - 1) / rpb8) * d.n_kv_heads;
-  bool big = blocks8 >= 512;
+  bool big = false;
   if (const char *env = getenv("IFKV_ATTN_WAVES")) big = atoi(env) == 8;
   const int rpb = big ? rpb8 : 128 / G;
   const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
