@@ -32,9 +32,10 @@ HBM_PEAK = 8.0e12        # B/s, MI355X HBM3E
 MFMA_BF16_PEAK = 2.5e15  # flop/s, dense bf16
 
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (scaled by the copy-kernel calibration); None until measured for the
-# workload below.  See profiles/.
-ATTENTION_TRAFFIC_BYTES = {}
+# runs, scaled by what the same counters read for the plain copy kernel
+# (profiles/attn_mfma_kernel_C3_ratio015_counters.md); None for workloads that
+# were not profiled.
+ATTENTION_TRAFFIC_BYTES = {("C3", 0.15): 8.682e8}
 
 
 def parse():
