@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kStatThreads) void score_stats_generic(const void *
 // normaliser over the prompt keys the row sees causally (rows 0..r).  Writes
 // (m, 1/Z).
 template <typename Tag, int D>
-__global__ __launch_bounds__(128) void score_merge_kernel(const float2 *__restrict__ partial, int n_slices,
+__global__ __launch_bounds__(64) void score_merge_kernel(const float2 *__restrict__ partial, int n_slices,
                                                           const void *__restrict__ q_prompt,
                                                           const void *__restrict__ k_prompt, int m_prompt,
                                                           int n_q_heads, int n_kv_heads, float sm_scale,
@@ -81,12 +81,25 @@ __global__ __launch_bounds__(128) void score_merge_kernel(const float2 *__restri
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n_q_heads * m_prompt) return;
   const int h = t / m_prompt, r = t - h * m_prompt;
+  // Slices are merged eight at a time: the eight loads are independent, so their latencies overlap.
   float m = -INFINITY, z = 0.f;
-  for (int s = 0; s < n_slices; ++s) {
-    const float2 p = partial[(static_cast<int64_t>(s) * n_q_heads + h) * m_prompt + r];
-    if (p.y > 0.f) {
-      const float mn = fmaxf(m, p.x);
-      z = z * expf(m - mn) + p.y * expf(p.x - mn);
+  for (int s0 = 0; s0 < n_slices; s0 += 8) {
+    float2 p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      p[u] = make_float2(-INFINITY, 0.f);
+      if (s0 + u < n_slices) p[u] = partial[(static_cast<int64_t>(s0 + u) * n_q_heads + h) * m_prompt + r];
+    }
+    float mn = m;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p[u].y > 0.f) mn = fmaxf(mn, p[u].x);
+    if (mn > -INFINITY) {
+      float acc = z * expf(m - mn);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (p[u].y > 0.f) acc += p[u].y * expf(p[u].x - mn);
+      z = acc;
       m = mn;
     }
   }
@@ -185,7 +198,7 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const
   hipLaunchKernelGGL((score_stats_generic<Tag, D>), ga, dim3(kStatThreads), 0, st, k_global, n_ctx, q_prompt,
                      m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, sl, partial);
   const int rows = d.n_q_heads * m_prompt;
-  hipLaunchKernelGGL((score_merge_kernel<Tag, D>), dim3((rows + 127) / 128), dim3(128), 0, st, partial, n_slices,
+  hipLaunchKernelGGL((score_merge_kernel<Tag, D>), dim3((rows + 63) / 64), dim3(64), 0, st, partial, n_slices,
                      q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
   hipLaunchKernelGGL((score_colsum_generic<Tag, D>), dim3(static_cast<unsigned>((n_ctx + kColThreads - 1) / kColThreads)),
                      dim3(kColThreads), 0, st, k_global, n_ctx, q_prompt, m_prompt, d.n_q_heads, d.n_kv_heads,
@@ -234,7 +247,7 @@ hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, cons
     float2 *partial = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.partial_off);
     float2 *stats = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.stats_off);
     const int rows = d.n_q_heads * m_prompt;
-    hipLaunchKernelGGL((score_merge_kernel<BF16Tag, 128>), dim3((rows + 127) / 128), dim3(128), 0, ctx->stream, partial,
+    hipLaunchKernelGGL((score_merge_kernel<BF16Tag, 128>), dim3((rows + 63) / 64), dim3(64), 0, ctx->stream, partial,
                        n_slices, q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
     return launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, true, accumulate, scores);
   }

@@ -32,6 +32,7 @@ constexpr int QSTR = D + 8;        // LDS row stride in elements (272 B: conflic
 constexpr int kQChunk = 512;       // query rows resident in LDS
 constexpr int kQBlocks = kQChunk / 32;
 constexpr int kThreads = 512;
+constexpr int kWpe = kThreads / 256;  // wavefronts per SIMD
 constexpr int kWaves = kThreads / 64;
 constexpr int kTile = 64;          // keys per wavefront step
 constexpr float kLog2e = 1.4426950408889634f;
@@ -57,13 +58,26 @@ __device__ __forceinline__ bool q_row_address(const ScoreGeom &gm, int g, int qc
 
 __device__ __forceinline__ void load_q_chunk(uint16_t *q_lds, const uint16_t *__restrict__ q_prompt,
                                              const ScoreGeom &gm, int g, int qc, int rows) {
-  for (int v = threadIdx.x; v < rows * (D / 8); v += kThreads) {
-    const int ql = v >> 4, c = v & 15;
-    int64_t off;
-    int h, r;
-    v4u x = {0u, 0u, 0u, 0u};
-    if (q_row_address(gm, g, qc, ql, &off, &h, &r)) x = *reinterpret_cast<const v4u *>(q_prompt + off + 8 * c);
-    *reinterpret_cast<v4u *>(&q_lds[ql * QSTR + 8 * c]) = x;
+  // eight independent 16-byte loads per thread are in flight before the first LDS store
+  constexpr int kInFlight = 8;
+  const int total = rows * (D / 8);
+  for (int v0 = threadIdx.x; v0 < total; v0 += kThreads * kInFlight) {
+    v4u x[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const int v = v0 + u * kThreads;
+      const int ql = v >> 4, c = v & 15;
+      int64_t off;
+      int h, r;
+      x[u] = v4u{0u, 0u, 0u, 0u};
+      if (v < total && q_row_address(gm, g, qc, ql, &off, &h, &r))
+        x[u] = *reinterpret_cast<const v4u *>(q_prompt + off + 8 * c);
+    }
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const int v = v0 + u * kThreads;
+      if (v < total) *reinterpret_cast<v4u *>(&q_lds[(v >> 4) * QSTR + 8 * (v & 15)]) = x[u];
+    }
   }
 }
 
@@ -80,10 +94,48 @@ __device__ __forceinline__ void load_k_frags(bf16x8 (&kf)[2][8], const uint16_t 
   }
 }
 
+// Query fragment s of 32-row block qb: lane (row, hf) holds columns 16 s + 8 hf .. +7 of row qb*32 + row.
+__device__ __forceinline__ bf16x8 q_frag(const uint16_t *q_lds, int qb, int s, int row, int hf) {
+  return __builtin_bit_cast(bf16x8,
+                            *reinterpret_cast<const v4u *>(&q_lds[(qb * 32 + row) * QSTR + 16 * s + 8 * hf]));
+}
+
+// Contraction step s of one 32-query block against the 64-key tile in `kf`.
+// KEYS_AS_ROWS selects the operand order: S^T = K.Q^T (pass A) or S = Q.K^T (pass B).
+template <bool KEYS_AS_ROWS>
+__device__ __forceinline__ void qk_step(f32x16 &S0, f32x16 &S1, const bf16x8 (&kf)[2][8], bf16x8 qf, int s) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (KEYS_AS_ROWS) {
+    S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][s], qf, s == 0 ? zero : S0, 0, 0, 0);
+    S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][s], qf, s == 0 ? zero : S1, 0, 0, 0);
+  } else {
+    S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[0][s], s == 0 ? zero : S0, 0, 0, 0);
+    S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[1][s], s == 0 ? zero : S1, 0, 0, 0);
+  }
+}
+
+// The same, one MFMA at a time (t = 0: keys 0..31 of the tile, t = 1: keys 32..63).
+template <bool KEYS_AS_ROWS>
+__device__ __forceinline__ void qk_half_step(f32x16 &S, const bf16x8 (&kf)[2][8], bf16x8 qf, int s, int t) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (KEYS_AS_ROWS)
+    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][s], qf, s == 0 ? zero : S, 0, 0, 0);
+  else
+    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[t][s], s == 0 ? zero : S, 0, 0, 0);
+}
+
+// A whole block with nothing interleaved (pipeline prologue).
+template <bool KEYS_AS_ROWS>
+__device__ __forceinline__ void qk_block(f32x16 &S0, f32x16 &S1, const bf16x8 (&kf)[2][8], const uint16_t *q_lds,
+                                         int qb, int row, int hf) {
+#pragma unroll
+  for (int s = 0; s < 8; ++s) qk_step<KEYS_AS_ROWS>(S0, S1, kf, q_frag(q_lds, qb, s, row, hf), s);
+}
+
 // ---------------------------------------------------------------------------
 // pass A
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_stats_mfma(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, kWpe))) void score_stats_mfma(
     const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm,
     float2 *__restrict__ partial) {
   __shared__ __attribute__((aligned(16))) uint16_t q_lds[kQChunk * QSTR];
@@ -93,9 +145,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   const int qc = blockIdx.y - g * gm.n_qchunks;
   const int q_total = gm.m_prompt * G;
   const int q_rows = min(kQChunk, q_total - qc * kQChunk);
-  const int nqb = (q_rows + 31) >> 5;
+  const int nqb = ((q_rows + 63) >> 6) << 1;  // 32-row query blocks, padded to an even count
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, hf = lane >> 5;
+
+  const float c = gm.scale_log2;
+  const int kv_begin = kb * gm.kv_per_block;
+  const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
+  // the first key tile is requested before the query tile is staged, so both travel together
+  bf16x8 kf[2][8];
+  int j0 = kv_begin + wave * kTile;
+  if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
 
   load_q_chunk(q_lds, q_prompt, gm, g, qc, nqb * 32);
   __syncthreads();
@@ -106,57 +166,70 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     m[qb] = -INFINITY;
     z[qb] = 0.f;
   }
-  const float c = gm.scale_log2;
-  const int kv_begin = kb * gm.kv_per_block;
-  const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
-  for (int j0 = kv_begin + wave * kTile; j0 < kv_end; j0 += kWaves * kTile) {
-    bf16x8 kf[2][8];
-    load_k_frags(kf, k_global, gm, g, j0, row, hf);
-    const bool tail = j0 + kTile > kv_end;
+  // register r of S_t: key j0 + 32 t + 8 (r/4) + 4 hf + r%4, query row qb*32 + (lane & 31)
+  //
+  // Software pipeline over the query blocks (their count is even).  pipe_step issues the sixteen
+  // MFMAs of block qn into (N0, N1) in eight slices of two; each slice is followed by a share of
+  // the vector work on the finished block (C0, C1): slice 0 takes the running maximum, slices
+  // 1..7 the exponentials and the sum.  The fences keep the slices in this order, so the matrix
+  // pipe works underneath the vector instructions of the same wavefront.  The last step of a
+  // tile issues one block whose products are not used.
+  auto pipe_step = [&](const bf16x8 (&kf)[2][8], f32x16 &N0, f32x16 &N1, int qn, f32x16 &C0, f32x16 &C1, float &mq,
+                       float &zq, int j0, bool tail) {
+    if (tail) {  // ragged last tile only
 #pragma unroll
-    for (int qb = 0; qb < kQBlocks; ++qb) {
-      if (qb < nqb) {
-        f32x16 S0, S1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          S0[r] = 0.f;
-          S1[r] = 0.f;
-        }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          const bf16x8 qf = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const v4u *>(&q_lds[(qb * 32 + row) * QSTR + 16 * s + 8 * hf]));
-          S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][s], qf, S0, 0, 0, 0);
-          S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][s], qf, S1, 0, 0, 0);
-        }
-        // register r of S_t: key j0 + 32 t + 8 (r/4) + 4 hf + r%4, query row qb*32 + (lane & 31)
-        if (tail) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kv = j0 + 8 * (r >> 2) + 4 * hf + (r & 3);
-            if (kv >= kv_end) S0[r] = -INFINITY;
-            if (kv + 32 >= kv_end) S1[r] = -INFINITY;
-          }
-        }
-        float mx = S0[0];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, fmaxf(S0[r], S1[r]));
-        const float m_new = fmaxf(m[qb], mx * c);
-        const float m_use = fmaxf(m_new, -1e30f);  // a lane that has seen no valid key yet stays at (-inf, 0)
-        float acc = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          acc += __builtin_amdgcn_exp2f(fmaf(S0[r], c, -m_use));
-          acc += __builtin_amdgcn_exp2f(fmaf(S1[r], c, -m_use));
-        }
-        z[qb] = z[qb] * __builtin_amdgcn_exp2f(m[qb] - m_use) + acc;
-        m[qb] = m_new;
+      for (int r = 0; r < 16; ++r) {
+        const int kv = j0 + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (kv >= kv_end) C0[r] = -INFINITY;
+        if (kv + 32 >= kv_end) C1[r] = -INFINITY;
       }
     }
+    float m_use = 0.f, m_new = 0.f, acc = 0.f;
+    bf16x8 qf = q_frag(q_lds, qn, 0, row, hf);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      bf16x8 qf_next = qf;
+      if (s < 7) qf_next = q_frag(q_lds, qn, s + 1, row, hf);
+      qk_step<true>(N0, N1, kf, qf, s);
+      if (s == 0) {
+        float mx = C0[0];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, fmaxf(C0[r], C1[r]));
+        m_new = fmaxf(mq, mx * c);
+        m_use = fmaxf(m_new, -1e30f);  // a lane that has seen no valid key yet stays at (-inf, 0)
+      } else {
+        // 32 values over seven slices: registers [lo, hi) of both halves
+        const int lo = ((s - 1) * 16) / 7, hi = (s * 16) / 7;
+#pragma unroll
+        for (int r = lo; r < hi; ++r) {
+          acc += __builtin_amdgcn_exp2f(fmaf(C0[r], c, -m_use));
+          acc += __builtin_amdgcn_exp2f(fmaf(C1[r], c, -m_use));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      qf = qf_next;
+    }
+    zq = zq * __builtin_amdgcn_exp2f(mq - m_use) + acc;
+    mq = m_new;
+  };
+  for (; j0 < kv_end; j0 += kWaves * kTile) {
+    const bool tail = j0 + kTile > kv_end;
+    f32x16 A0, A1, B0, B1;
+    qk_block<true>(A0, A1, kf, q_lds, 0, row, hf);
+#pragma unroll
+    for (int qb = 0; qb < kQBlocks; qb += 2) {
+      if (qb < nqb) {
+        pipe_step(kf, B0, B1, qb + 1, A0, A1, m[qb], z[qb], j0, tail);
+        pipe_step(kf, A0, A1, min(qb + 2, nqb - 1), B0, B1, m[qb + 1], z[qb + 1], j0, tail);
+      }
+    }
+    const int j_next = j0 + kWaves * kTile;
+    if (j_next < kv_end) load_k_frags(kf, k_global, gm, g, j_next, row, hf);
   }
 
   // merge the two lane halves (same query row, disjoint keys), then the wavefronts
-  __syncthreads();  // every wavefront is done with the query tile: LDS is reused below
+  __syncthreads();
+  // every wavefront is done with the query tile: LDS is reused below
   float2 *w_stats = reinterpret_cast<float2 *>(q_lds);  // [kWaves][kQChunk]
 #pragma unroll
   for (int qb = 0; qb < kQBlocks; ++qb) {
@@ -191,7 +264,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 // ---------------------------------------------------------------------------
 // pass B
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_colsum_mfma(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, kWpe))) void score_colsum_mfma(
     const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm,
     const float2 *__restrict__ stats, float *__restrict__ colpart) {
   __shared__ __attribute__((aligned(16))) uint16_t q_lds[kQChunk * QSTR];
@@ -202,9 +275,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   const int qc = blockIdx.y - g * gm.n_qchunks;
   const int q_total = gm.m_prompt * G;
   const int q_rows = min(kQChunk, q_total - qc * kQChunk);
-  const int nqb = (q_rows + 31) >> 5;
+  const int nqb = ((q_rows + 63) >> 6) << 1;  // 32-row query blocks, padded to an even count
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, hf = lane >> 5;
+  const float c = gm.scale_log2;
+  const int kv_begin = kb * gm.kv_per_block;
+  const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
+  // the first key tile is requested before the query tile is staged, so both travel together
+  bf16x8 kf[2][8];
+  int j0 = kv_begin + wave * kTile;
+  if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
 
   load_q_chunk(q_lds, q_prompt, gm, g, qc, nqb * 32);
   for (int ql = threadIdx.x; ql < nqb * 32; ql += kThreads) {
@@ -219,38 +299,68 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   }
   __syncthreads();
 
-  const float c = gm.scale_log2;
-  const int kv_begin = kb * gm.kv_per_block;
-  const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
   float *dst = colpart + static_cast<int64_t>(blockIdx.y) * gm.n_ctx;
-  for (int j0 = kv_begin + wave * kTile; j0 < kv_end; j0 += kWaves * kTile) {
-    bf16x8 kf[2][8];
-    load_k_frags(kf, k_global, gm, g, j0, row, hf);
+  // register r of S_t: query row qb*32 + 8 (r/4) + 4 hf + r%4, key j0 + 32 t + (lane & 31)
+  //
+  // Software pipeline over the query blocks (their count is even).  pipe_step issues the sixteen
+  // MFMAs of block qn into (N0, N1) in eight slices of two; each slice is followed by the
+  // exponentials of four values of the finished block qc in (C0, C1).  The fences keep the slices
+  // in this order, so the matrix pipe works underneath the vector instructions of the same
+  // wavefront.  The last step of a tile issues one block whose products are not used.
+  // qf is a ring of four query fragments: on entry it holds contraction steps 0..2 of block qn;
+  // step s requests the fragment three steps ahead (of block qn, then of the block after it, qn2),
+  // so an LDS read has three slices of work to hide behind.  bn receives the softmax offsets of
+  // block qn, which the next call consumes as bc.
+  auto pipe_step = [&](const bf16x8 (&kf)[2][8], bf16x8 (&qf)[4], f32x16 &N0, f32x16 &N1, int qn, int qn2,
+                       const f32x16 &C0, const f32x16 &C1, const f32x4 (&bc)[4], f32x4 (&bn)[4], float &col0,
+                       float &col1) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      qf[(s + 3) & 3] = s + 3 < 8 ? q_frag(q_lds, qn, s + 3, row, hf) : q_frag(q_lds, qn2, s + 3 - 8, row, hf);
+      if ((s & 1) == 0) bn[s >> 1] = *reinterpret_cast<const f32x4 *>(&b_lds[qn * 32 + 8 * (s >> 1) + 4 * hf]);
+      // MFMA, two values, MFMA, two values: each MFMA finds the matrix pipe free
+      qk_half_step<false>(N0, kf, qf[s & 3], s, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int e = 2 * (s & 1);
+        col0 += __builtin_amdgcn_exp2f(fmaf(C0[4 * (s >> 1) + e], c, -bc[s >> 1][e]));
+        col1 += __builtin_amdgcn_exp2f(fmaf(C1[4 * (s >> 1) + e], c, -bc[s >> 1][e]));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      qk_half_step<false>(N1, kf, qf[s & 3], s, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int e = 2 * (s & 1) + 1;
+        col0 += __builtin_amdgcn_exp2f(fmaf(C0[4 * (s >> 1) + e], c, -bc[s >> 1][e]));
+        col1 += __builtin_amdgcn_exp2f(fmaf(C1[4 * (s >> 1) + e], c, -bc[s >> 1][e]));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  for (; j0 < kv_end; j0 += kWaves * kTile) {
+    // the next tile's fragments travel while this one is processed
+    bf16x8 kf_next[2][8];
+    const int j_next = j0 + kWaves * kTile;
+    if (j_next < kv_end) load_k_frags(kf_next, k_global, gm, g, j_next, row, hf);
     float col0 = 0.f, col1 = 0.f;
-    for (int qb = 0; qb < nqb; ++qb) {
-      f32x16 S0, S1;
+    f32x16 A0, A1, B0, B1;
+    f32x4 ba[4], bb[4];
+    bf16x8 qf[4];
+    qk_block<false>(A0, A1, kf, q_lds, 0, row, hf);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        S0[r] = 0.f;
-        S1[r] = 0.f;
-      }
+    for (int ri = 0; ri < 4; ++ri) ba[ri] = *reinterpret_cast<const f32x4 *>(&b_lds[8 * ri + 4 * hf]);
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const bf16x8 qf = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const v4u *>(&q_lds[(qb * 32 + row) * QSTR + 16 * s + 8 * hf]));
-        S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[0][s], S0, 0, 0, 0);
-        S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[1][s], S1, 0, 0, 0);
-      }
-      // register r: query row qb*32 + 8 (r/4) + 4 hf + r%4, key j0 + 32 t + (lane & 31)
+    for (int s = 0; s < 3; ++s) qf[s] = q_frag(q_lds, 1, s, row, hf);
+    for (int qb = 0; qb < nqb; qb += 2) {
+      const int q2 = min(qb + 2, nqb - 1), q3 = min(qb + 3, nqb - 1);
+      pipe_step(kf, qf, B0, B1, qb + 1, q2, A0, A1, ba, bb, col0, col1);
+      pipe_step(kf, qf, A0, A1, q2, q3, B0, B1, bb, ba, col0, col1);
+    }
+    if (j_next < kv_end) {
 #pragma unroll
-      for (int ri = 0; ri < 4; ++ri) {
-        const f32x4 b = *reinterpret_cast<const f32x4 *>(&b_lds[qb * 32 + 8 * ri + 4 * hf]);
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          col0 += __builtin_amdgcn_exp2f(fmaf(S0[4 * ri + e], c, -b[e]));
-          col1 += __builtin_amdgcn_exp2f(fmaf(S1[4 * ri + e], c, -b[e]));
-        }
-      }
+        for (int s2 = 0; s2 < 8; ++s2) kf[t][s2] = kf_next[t][s2];
     }
     col0 += __shfl_xor(col0, 32, 64);
     col1 += __shfl_xor(col1, 32, 64);

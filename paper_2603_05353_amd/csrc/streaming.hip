@@ -5,13 +5,15 @@
 #include "ifkv_device.h"
 #include "ifkv_internal.h"
 
+
 namespace ifkv {
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRepoRows = 16;  // rows per tile
 constexpr int kBatch = 4;      // independent 16-byte loads in flight per thread and stream
+constexpr int kRepoRows = 8;   // stage 1: rows per tile (16 KiB of keys and of values at 8 x 128 bf16)
+constexpr int kRepoBatch = 4;  // stage 1: work items per thread and batch, four 16-byte loads each
 
 // ---------------------------------------------------------------------------
 // Stage 1.  Method, Eq. (5): global position = chunk start + local index; a
@@ -19,10 +21,33 @@ constexpr int kBatch = 4;      // independent 16-byte loads in flight per thread
 // 2-D pair j is turned by advance * theta_j (Eq. 3-4; rotations add).
 // The advance is per chunk, so a block needs d/2 (cos, sin) values only; they
 // are formed in fp64 by the first d/2 threads and shared through LDS.
+//
+// A block owns kRepoRows rows of one chunk.  It requests its key vectors and
+// the matching value vectors before anything else, forms the (cos, sin) table
+// while those loads are in flight, and then rotates and stores.
 // ---------------------------------------------------------------------------
-template <typename Tag, int PAIRING>
+
+// Row copy of `total` 16-byte vectors, kBatch loads in flight per thread.
+__device__ __forceinline__ void copy_vectors(const v4u *__restrict__ src, v4u *__restrict__ dst, int total,
+                                             int tid) {
+  for (int base = tid; base < total; base += kThreads * kBatch) {
+    v4u x[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int it = base + u * kThreads;
+      if (it < total) x[u] = __builtin_nontemporal_load(src + it);
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int it = base + u * kThreads;
+      if (it < total) __builtin_nontemporal_store(x[u], dst + it);
+    }
+  }
+}
+
+template <typename Tag, int PAIRING, int RB>
 __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const double *__restrict__ inv_freq,
-                                                              int n_kv_heads, int head_dim,
+                                                              int rows_per_tile, int n_kv_heads, int head_dim,
                                                               v4u *__restrict__ k_out,
                                                               v4u *__restrict__ v_out) {
   using E = Elem<Tag>;
@@ -30,68 +55,81 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
   __shared__ float s_cos[kMaxHeadDim / 2];
   __shared__ float s_sin[kMaxHeadDim / 2];
 
+  // Chunk of this tile: first-tile indices ascend, so the chunk is the number of entries not above
+  // the tile index, minus one.  One lane per entry, one ballot.
   const int tile = blockIdx.x;
-  int ci = 0;
-  for (int i = 1; i < b.n; ++i)
-    if (tile >= b.c[i].tile0) ci = i;
+  const int lane = threadIdx.x & 63;
+  const int first = lane < b.n ? b.c[lane].tile0 : 0x7fffffff;
+  const int ci = __builtin_amdgcn_readfirstlane(__popcll(__ballot(tile >= first)) - 1);
   const RepoChunk c = b.c[ci];
-  const int row0 = (tile - c.tile0) * kRepoRows;
-  const int nrows = min(kRepoRows, c.len - row0);
+  const int row0 = (tile - c.tile0) * rows_per_tile;
+  const int nrows = min(rows_per_tile, c.len - row0);
   if (nrows <= 0) return;
 
   const int tid = threadIdx.x;
   const int half = head_dim / 2;
-  const bool identity = (c.advance == 0.0);
-  if (!identity && tid < half) {
-    double sn, cs;
-    sincos(c.advance * inv_freq[tid], &sn, &cs);
-    s_cos[tid] = static_cast<float>(cs);
-    s_sin[tid] = static_cast<float>(sn);
-  }
-  __syncthreads();
-
   const int row_vecs = n_kv_heads * head_dim / VE;  // 16-byte vectors per row
+  const int total_vecs = nrows * row_vecs;          // rows are contiguous: the tile is one flat range
   const v4u *k_src = reinterpret_cast<const v4u *>(c.k) + static_cast<int64_t>(row0) * row_vecs;
   v4u *k_dst = k_out + (c.dst_row + row0) * row_vecs;
+  const bool has_v = c.v != nullptr && v_out != nullptr;
+  const v4u *v_src = has_v ? reinterpret_cast<const v4u *>(c.v) + static_cast<int64_t>(row0) * row_vecs : nullptr;
+  v4u *v_dst = has_v ? v_out + (c.dst_row + row0) * row_vecs : nullptr;
 
-  if (identity) {
-    const int total = nrows * row_vecs;
-    for (int base = tid; base < total; base += kThreads * kBatch) {
-      v4u x[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
-        if (it < total) x[u] = __builtin_nontemporal_load(k_src + it);
-      }
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
-        if (it < total) __builtin_nontemporal_store(x[u], k_dst + it);
-      }
+  if (c.advance == 0.0) {  // already at its global phase: both tensors are plain row copies
+    copy_vectors(k_src, k_dst, total_vecs, tid);
+    if (has_v) copy_vectors(v_src, v_dst, total_vecs, tid);
+    return;
+  }
+
+  // Every thread walks the same number of batches, so the barrier after the first load phase is
+  // reached by all of them.
+  bool table_ready = false;
+  auto build_table = [&]() {
+    if (table_ready) return;
+    if (tid < half) {
+      double sn, cs;
+      sincos(c.advance * inv_freq[tid], &sn, &cs);
+      s_cos[tid] = static_cast<float>(cs);
+      s_sin[tid] = static_cast<float>(sn);
     }
-  } else if (PAIRING == IFKV_ROPE_HALF) {
-    const int hv = half / VE;            // vectors per half head
-    const int items_per_row = n_kv_heads * hv;
-    const int total = nrows * items_per_row;
-    for (int base = tid; base < total; base += kThreads * kBatch) {
-      v4u lo[kBatch], hi[kBatch];
-      int off[kBatch], cc[kBatch];
+    __syncthreads();
+    table_ready = true;
+  };
+
+  if (PAIRING == IFKV_ROPE_HALF) {
+    // Work item = vector cc of the low half of one (row, head) slice plus its partner in the high
+    // half.  The slices of a tile are contiguous, so slice = item / hv and hv is a power of two.
+    const int hv = half / VE;  // vectors per half head: 4, 8 or 16
+    const int hv_shift = __builtin_ctz(hv);
+    const int total = total_vecs >> 1;
+    for (int base0 = 0; base0 < total; base0 += kThreads * RB) {
+      v4u lo[RB], hi[RB], vlo[RB], vhi[RB];
+      int off[RB], cc[RB];
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
+      for (int u = 0; u < RB; ++u) {
+        const int it = base0 + tid + u * kThreads;
+        cc[u] = it & (hv - 1);
+        off[u] = ((it >> hv_shift) << (hv_shift + 1)) + cc[u];
         if (it < total) {
-          const int r = it / items_per_row;
-          const int w = it - r * items_per_row;
-          const int h = w / hv;
-          cc[u] = w - h * hv;
-          off[u] = r * row_vecs + h * 2 * hv + cc[u];
           lo[u] = __builtin_nontemporal_load(k_src + off[u]);
           hi[u] = __builtin_nontemporal_load(k_src + off[u] + hv);
         }
       }
+      if (has_v) {
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
+        for (int u = 0; u < RB; ++u) {
+          const int it = base0 + tid + u * kThreads;
+          if (it < total) {
+            vlo[u] = __builtin_nontemporal_load(v_src + off[u]);
+            vhi[u] = __builtin_nontemporal_load(v_src + off[u] + hv);
+          }
+        }
+      }
+      build_table();
+#pragma unroll
+      for (int u = 0; u < RB; ++u) {
+        const int it = base0 + tid + u * kThreads;
         if (it < total) {
           float a[VE], bb[VE], ra[VE], rb[VE];
           E::unpack(lo[u], a);
@@ -107,22 +145,35 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
           __builtin_nontemporal_store(E::pack(rb), k_dst + off[u] + hv);
         }
       }
-    }
-  } else {  // interleaved pairs (x_{2i}, x_{2i+1})
-    const int head_vecs = head_dim / VE;
-    const int total = nrows * row_vecs;
-    for (int base = tid; base < total; base += kThreads * kBatch) {
-      v4u x[kBatch];
+      if (has_v) {
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
-        if (it < total) x[u] = __builtin_nontemporal_load(k_src + it);
+        for (int u = 0; u < RB; ++u) {
+          const int it = base0 + tid + u * kThreads;
+          if (it < total) {
+            __builtin_nontemporal_store(vlo[u], v_dst + off[u]);
+            __builtin_nontemporal_store(vhi[u], v_dst + off[u] + hv);
+          }
+        }
       }
+    }
+  } else {  // interleaved pairs (x_{2i}, x_{2i+1}): a vector holds VE/2 whole pairs
+    const int head_vecs = head_dim / VE;  // power of two
+    for (int base0 = 0; base0 < total_vecs; base0 += kThreads * RB) {
+      v4u x[RB], y[RB];
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
-        if (it < total) {
-          const int pair0 = ((it % row_vecs) % head_vecs) * (VE / 2);
+      for (int u = 0; u < RB; ++u) {
+        const int it = base0 + tid + u * kThreads;
+        if (it < total_vecs) {
+          x[u] = __builtin_nontemporal_load(k_src + it);
+          if (has_v) y[u] = __builtin_nontemporal_load(v_src + it);
+        }
+      }
+      build_table();
+#pragma unroll
+      for (int u = 0; u < RB; ++u) {
+        const int it = base0 + tid + u * kThreads;
+        if (it < total_vecs) {
+          const int pair0 = (it & (head_vecs - 1)) * (VE / 2);
           float f[VE], r[VE];
           E::unpack(x[u], f);
 #pragma unroll
@@ -133,27 +184,8 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
             r[2 * e + 1] = fmaf(f[2 * e], sn, f[2 * e + 1] * cs);
           }
           __builtin_nontemporal_store(E::pack(r), k_dst + it);
+          if (has_v) __builtin_nontemporal_store(y[u], v_dst + it);
         }
-      }
-    }
-  }
-
-  // Values carry no rotary phase: plain row copy into the same rows.
-  if (c.v != nullptr && v_out != nullptr) {
-    const v4u *v_src = reinterpret_cast<const v4u *>(c.v) + static_cast<int64_t>(row0) * row_vecs;
-    v4u *v_dst = v_out + (c.dst_row + row0) * row_vecs;
-    const int total = nrows * row_vecs;
-    for (int base = tid; base < total; base += kThreads * kBatch) {
-      v4u x[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
-        if (it < total) x[u] = __builtin_nontemporal_load(v_src + it);
-      }
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int it = base + u * kThreads;
-        if (it < total) __builtin_nontemporal_store(x[u], v_dst + it);
       }
     }
   }
@@ -223,9 +255,9 @@ hipError_t launch_reposition(ifkv_ctx *ctx, const RepoBatch &batch, void *k_out,
   dim3 grid(batch.total_tiles), block(kThreads);
   v4u *ko = reinterpret_cast<v4u *>(k_out);
   v4u *vo = reinterpret_cast<v4u *>(v_out);
-#define IFKV_LAUNCH_REPO(TAG, PAIR)                                                            \
-  hipLaunchKernelGGL((reposition_kernel<TAG, PAIR>), grid, block, 0, ctx->stream, batch,        \
-                     ctx->d_inv_freq, d.n_kv_heads, d.head_dim, ko, vo)
+#define IFKV_LAUNCH_REPO(TAG, PAIR)                                                              \
+  hipLaunchKernelGGL((reposition_kernel<TAG, PAIR, kRepoBatch>), grid, block, 0, ctx->stream,    \
+                     batch, ctx->d_inv_freq, kRepoRows, d.n_kv_heads, d.head_dim, ko, vo)
   if (d.dtype == IFKV_BF16) {
     if (d.pairing == IFKV_ROPE_HALF)
       IFKV_LAUNCH_REPO(BF16Tag, IFKV_ROPE_HALF);

@@ -335,8 +335,8 @@ hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_
   hipStream_t st = ctx->stream;
   if (n <= 256 * 32) {
     hipLaunchKernelGGL((topk_resident_kernel<256, 1>), dim3(1), dim3(256), 0, st, scores, n, kk, idx_out);
-  } else if (n <= 256 * 32 * 4) {
-    hipLaunchKernelGGL((topk_resident_kernel<256, 4>), dim3(1), dim3(256), 0, st, scores, n, kk, idx_out);
+  } else if (n <= 1024 * 32) {
+    hipLaunchKernelGGL((topk_resident_kernel<1024, 1>), dim3(1), dim3(1024), 0, st, scores, n, kk, idx_out);
   } else {
     hipLaunchKernelGGL(topk_streaming_kernel, dim3(1), dim3(kStreamThreads), 0, st, scores, n, kk, idx_out);
   }
