@@ -67,6 +67,12 @@ typedef enum { IFKV_ROPE_HALF = 0, IFKV_ROPE_INTERLEAVED = 1 } ifkv_rope_pairing
 /* Route every stage through the plain fp32 ALU kernels even where a bf16 MFMA
  * kernel exists (cross-checking and debugging). */
 #define IFKV_FLAG_FORCE_GENERIC 1u
+/* Stage 4, bf16, head_dim 128: use the one-wavefront-per-SIMD kernel (64 query
+ * columns per wavefront, software-pipelined over half tiles) instead of the
+ * default two-wavefront kernel.  Same results to the stage's tolerance; an
+ * alternative schedule kept for tuning, not the faster one at the measured
+ * shapes. */
+#define IFKV_FLAG_ATTN_WIDE 2u
 
 typedef struct {
   int32_t dtype;      /* ifkv_dtype of K, V, Q and attention outputs */

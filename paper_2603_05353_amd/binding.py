@@ -21,6 +21,7 @@ IFKV_OK, IFKV_EINVAL, IFKV_ESHAPE, IFKV_EDTYPE, IFKV_ENOMEM, IFKV_EHIP = 0, -1, 
 IFKV_F32, IFKV_BF16 = 0, 1
 IFKV_ROPE_HALF, IFKV_ROPE_INTERLEAVED = 0, 1
 IFKV_FLAG_FORCE_GENERIC = 1
+IFKV_FLAG_ATTN_WIDE = 2
 
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",

@@ -322,11 +322,10 @@ struct Column {
   int64_t q_off;
 };
 
+// qc: this lane's query column within the block (columns are numbered row-major over (row, head in group)).
 __device__ __forceinline__ Column setup_column(const int32_t *__restrict__ row_pos, int n_rows, int n_kv, int row0,
-                                               int rows_per_block, int G, int g, int n_q_heads) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+                                               int rows_per_block, int G, int g, int n_q_heads, int qc) {
   Column c;
-  const int qc = wave * 32 + (lane & 31);
   const int rr = qc / G;
   c.hh = qc - rr * G;
   c.row = row0 + rr;
@@ -408,7 +407,8 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   const int G = n_q_heads / n_kv_heads;
   const int g = blockIdx.x;
   const int rb = gridDim.y - 1 - blockIdx.y;  // longest prefixes are dispatched first
-  const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads);
+  const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
+                                (threadIdx.x >> 6) * 32 + (lane & 31));
   bf16x8 qf[8];
   load_q_frags(qf, q_sel, c, hf);
   const int n_tiles = block_tiles<NWAVES>(c.p_wmax, s_pmax);
@@ -460,6 +460,298 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   write_output(w, c, out, lse_out, n_q_heads, g, G, hf);
 }
 
+
+// ---------------------------------------------------------------------------
+// Wide kernel: ONE wavefront per SIMD, 64 query columns per wavefront (two blocks, A and B, of
+// 32), four wavefronts = 256 columns per block.
+//
+// The 128-column kernel above saturates the LDS read path: every K and V fragment read from LDS
+// feeds a single MFMA.  Here each fragment feeds two (one per column block), which halves the LDS
+// bytes per flop.  With one wavefront per SIMD nothing else hides the exponentials, so the kv loop
+// is software-pipelined by hand over HALF tiles of 32 kv rows (which keeps the logits of two
+// half tiles, for two column blocks, within the register file).  Step j issues, as one
+// instruction stream of 32 slots,
+//     slot  0..15   O^T += V(j-1)^T . P(j-1)^T   for A and B   (V fragment read once, used twice)
+//     slot 16..31   S(j+1)^T = K(j+1) . Q^T      for A and B   (K fragment read once, used twice)
+// and after the MFMA of slot n the n-th piece of the softmax of half tile j (block A in slots
+// 0..15, block B in slots 16..31): running max, exponentials, row sums, bf16 packing.  The fences
+// keep this order, so the matrix pipe runs underneath the vector work of the same wavefront.
+// A rescale of O that half tile j asks for is applied after the last MFMA of half tile j-1 on
+// that accumulator (it must scale those contributions too) and before step j+1 adds half tile j.
+//
+// LDS: ring of four 64-row stages; while tile i is being processed tiles i-1 (V), i and i+1 (K)
+// are read and tile i+2 is being written by the direct loads.
+// ---------------------------------------------------------------------------
+constexpr int kWideStages = 4;
+constexpr int kVAhead = 3;  // V operands requested ahead (two transpose reads each)
+constexpr int kKAhead = 3;  // K operands requested ahead
+
+
+// The first product of the wide kernel is emitted as inline assembly so that the register file
+// split is explicit: query fragments (64 registers, read by nothing but these MFMAs) in the
+// accumulation half of the register file, logits in the vector half where the softmax reads them.
+// Left to itself the compiler chooses the opposite and pays 5 register copies per MFMA.  It cannot
+// see what this statement is, so the wait states the ISA asks for between an MFMA and a vector
+// instruction that reads its result are kept by construction in the pipelined step (the logits are
+// read one step later) and by an explicit s_nop in the plain routine.
+__device__ __forceinline__ void mfma_s(f32x16 &s_acc, v4u a, v4u q, bool first) {  // S (+)= a . q
+  if (first)
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(s_acc) : "v"(a), "a"(q));
+  else
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s_acc) : "v"(a), "a"(q));
+}
+
+struct SoftmaxTmp {
+  float mx, alpha, psum0, psum1;
+  bool rescale;
+};
+struct PHalf {
+  v4u step[2];  // contraction step u of the half tile: kv rows 16 u + 8 hf + 0..7
+};
+
+// Piece C (0..15) of the softmax of one half tile for one 32-column block.  Register r of S is kv
+// row jbase + 16 (r / 8) + 8 hf + r % 8.  Only piece 0 may branch (wavefront-uniform, and it is the
+// first piece of a step): the other pieces must stay in one basic block with the MFMAs they are
+// interleaved with.
+__device__ __forceinline__ void softmax_piece(int C, f32x16 &S, WaveState &w, PHalf &P, SoftmaxTmp &t, int jbase,
+                                              int p_q, int p_wmin, int hf, float scale_log2) {
+  if (C < 2) {  // running maximum over registers 8 C .. 8 C + 7; piece 0 applies the causal mask first
+    if (C == 0 && jbase + 31 > p_wmin) {
+      const int base = jbase + 8 * hf - p_q;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (base + 16 * (r >> 3) + (r & 7) > 0) S[r] = -INFINITY;
+    }
+    // three-input maximum as one instruction (the logits come out of an assembly statement, so
+    // fmaxf would first re-canonicalise every one of them)
+    float mx = C == 0 ? S[0] : t.mx;
+#pragma unroll
+    for (int r = 0; r < 8; r += 2)
+      asm("v_max3_f32 %0, %1, %2, %3" : "=v"(mx) : "v"(mx), "v"(S[8 * C + r]), "v"(S[8 * C + r + 1]));
+    t.mx = mx;
+  } else if (C == 2) {
+    const float mx = half_swap_max(t.mx);
+    const float m_new = fmaxf(w.m_run, mx * scale_log2);
+    t.rescale = __any(m_new > w.m_run + kSlack);
+    const float m_upd = t.rescale ? m_new : w.m_run;  // wavefront-uniform choice: a select, no branch
+    // 1 when nothing changes, 0 on the first tile (m_run = -inf); a lane that has seen only masked
+    // values keeps m_run = m_upd = -inf, where the difference is undefined: it has nothing to scale
+    t.alpha = m_upd == w.m_run ? 1.f : __builtin_amdgcn_exp2f(w.m_run - m_upd);
+    w.l_run *= t.alpha;
+    w.m_run = m_upd;
+    t.psum0 = 0.f;
+    t.psum1 = 0.f;
+  } else if (C < 11) {  // exponentials of two values
+    const int r = 2 * (C - 3);
+    S[r] = __builtin_amdgcn_exp2f(fmaf(S[r], scale_log2, -w.m_run));
+    S[r + 1] = __builtin_amdgcn_exp2f(fmaf(S[r + 1], scale_log2, -w.m_run));
+    t.psum0 += S[r];
+    t.psum1 += S[r + 1];
+  } else if (C < 15) {  // bf16 packing of half a contraction step
+    const int q = C - 11, u = q >> 1, h = q & 1, r0 = 8 * u + 4 * h;
+    P.step[u][2 * h + 0] = pack_bf16x2(S[r0 + 0], S[r0 + 1]);
+    P.step[u][2 * h + 1] = pack_bf16x2(S[r0 + 2], S[r0 + 3]);
+  } else {
+    w.l_run += t.psum0 + t.psum1;
+  }
+}
+
+__device__ __forceinline__ void apply_rescale(WaveState &w, const SoftmaxTmp &t) {
+  if (t.rescale) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) w.O[dt][r] *= t.alpha;
+  }
+}
+
+struct WideLane {
+  int pA, pB, p_wminA, p_wminB, hf;  // p_wmin*: smallest position among the block's valid columns
+  float scale_log2;
+};
+
+// One pipelined step (see the header above).  Pp*: P of half tile j-1 (consumed), Pc*: P of half
+// tile j (produced), Sc*: S of half tile j (consumed), Sn*: S of half tile j+1 (produced).
+// v_prev: V stage of half tile j-1, whose half is vh; k_next: K stage of half tile j+1, half kh.
+__device__ __forceinline__ void wide_step(WaveState &wA, WaveState &wB, const v4u (&qA)[8], const v4u (&qB)[8],
+                                          const PHalf &PpA, const PHalf &PpB, PHalf &PcA, PHalf &PcB, f32x16 &ScA,
+                                          f32x16 &ScB, f32x16 &SnA, f32x16 &SnB, const uint16_t *v_prev, int vh,
+                                          const uint16_t *k_next, int kh, const ReadOffsets &ro, const WideLane &ln,
+                                          int jbase) {
+  SoftmaxTmp tA, tB;
+  s16x4 vlo[kVAhead], vhi[kVAhead];
+  v4u kf[kKAhead];
+  const uint16_t *kp = k_next + kh * (32 * D);
+#pragma unroll
+  for (int x = 0; x < kVAhead; ++x) v_read(vlo[x], vhi[x], v_prev, ro, 8 * vh + x);
+  __builtin_amdgcn_sched_barrier(0);
+  // slots 0..15: second product of half tile j-1, softmax of half tile j for block A
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    const int u = x >> 2, dt = x & 3;
+    const s16x8 a16 = __builtin_shufflevector(vlo[x % kVAhead], vhi[x % kVAhead], 0, 1, 2, 3, 4, 5, 6, 7);
+    const bf16x8 a = __builtin_bit_cast(bf16x8, a16);
+    wA.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, PpA.step[u]), wA.O[dt], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_piece(2 * x, ScA, wA, PcA, tA, jbase, ln.pA, ln.p_wminA, ln.hf, ln.scale_log2);
+    __builtin_amdgcn_sched_barrier(0);
+    wB.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, PpB.step[u]), wB.O[dt], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_piece(2 * x + 1, ScA, wA, PcA, tA, jbase, ln.pA, ln.p_wminA, ln.hf, ln.scale_log2);
+    if (x + kVAhead < 8) v_read(vlo[x % kVAhead], vhi[x % kVAhead], v_prev, ro, 8 * vh + x + kVAhead);
+    if (x >= 8 - kKAhead) {  // first K operands of the next phase
+      const int s = x - (8 - kKAhead);
+      kf[s] = *reinterpret_cast<const v4u *>(&kp[ro.k[s]]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // The results of the pieces are only needed by a later step; this empty statement "uses" them
+  // here, so the compiler cannot sink the pieces out of the slots, past the branch below.
+  asm volatile("" ::"v"(PcA.step[0]), "v"(PcA.step[1]), "v"(wA.l_run), "v"(wA.m_run));
+  // the rescale half tile j asked for in block A: after the last MFMA of half tile j-1 on O_A
+  apply_rescale(wA, tA);
+  __builtin_amdgcn_sched_barrier(0);
+  // slots 16..31: first product of half tile j+1, softmax of half tile j for block B
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const v4u a = kf[s % kKAhead];
+    mfma_s(SnA, a, qA[s], s == 0);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_piece(2 * s, ScB, wB, PcB, tB, jbase, ln.pB, ln.p_wminB, ln.hf, ln.scale_log2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_s(SnB, a, qB[s], s == 0);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_piece(2 * s + 1, ScB, wB, PcB, tB, jbase, ln.pB, ln.p_wminB, ln.hf, ln.scale_log2);
+    if (s + kKAhead < 8) kf[s % kKAhead] = *reinterpret_cast<const v4u *>(&kp[ro.k[s + kKAhead]]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  asm volatile("" ::"v"(PcB.step[0]), "v"(PcB.step[1]), "v"(wB.l_run), "v"(wB.m_run));
+  apply_rescale(wB, tB);
+}
+
+// Not pipelined: first product of one half tile for both blocks (prologue).
+__device__ __forceinline__ void wide_qk(f32x16 &SA, f32x16 &SB, const v4u (&qA)[8], const v4u (&qB)[8],
+                                        const uint16_t *k_stage, int kh, const ReadOffsets &ro) {
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const v4u a = *reinterpret_cast<const v4u *>(&k_stage[ro.k[s] + kh * (32 * D)]);
+    mfma_s(SA, a, qA[s], s == 0);
+    mfma_s(SB, a, qB[s], s == 0);
+  }
+  asm volatile("s_nop 15\n\ts_nop 15");  // the logits are read by vector instructions next
+}
+
+// Not pipelined: second product of one half tile for both blocks (epilogue).
+__device__ __forceinline__ void wide_pv(WaveState &wA, WaveState &wB, const PHalf &PA, const PHalf &PB,
+                                        const uint16_t *v_stage, int vh, const ReadOffsets &ro) {
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    const int u = x >> 2, dt = x & 3;
+    s16x4 lo, hi;
+    v_read(lo, hi, v_stage, ro, 8 * vh + x);
+    const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    wA.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, PA.step[u]), wA.O[dt], 0, 0, 0);
+    wB.O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, PB.step[u]), wB.O[dt], 0, 0, 0);
+  }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_wide_kernel(
+    const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ row_pos, int n_rows,
+    const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache, int n_kv,
+    uint16_t *__restrict__ out, float *__restrict__ lse_out, int n_q_heads, int n_kv_heads, float scale_log2,
+    int rows_per_block) {
+  constexpr int NW = 4, NS = kWideStages;
+  __shared__ __attribute__((aligned(1024))) uint16_t k_lds[NS][TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) uint16_t v_lds[NS][TILE_ELEMS];
+  __shared__ int s_pmax[NW];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hf = lane >> 5;
+  const int G = n_q_heads / n_kv_heads;
+  const int g = blockIdx.x;
+  const int rb = gridDim.y - 1 - blockIdx.y;  // longest prefixes are dispatched first
+  const int row0 = rb * rows_per_block;
+  const Column cA = setup_column(row_pos, n_rows, n_kv, row0, rows_per_block, G, g, n_q_heads, wave * 64 + (lane & 31));
+  const Column cB =
+      setup_column(row_pos, n_rows, n_kv, row0, rows_per_block, G, g, n_q_heads, wave * 64 + 32 + (lane & 31));
+  // Query fragments go from memory straight into the accumulation half of the register file; the
+  // compiler does not know these loads are pending: the vmcnt(0) wait before the first barrier below
+  // covers them.  Columns without a row read a clamped (valid) row and are never written back.
+  v4u qA[8], qB[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(qA[x]) : "v"(q_sel + cA.q_off + 16 * x + 8 * hf) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(qB[x]) : "v"(q_sel + cB.q_off + 16 * x + 8 * hf) : "memory");
+  }
+  const int n_tiles = block_tiles<NW>(max(cA.p_wmax, cB.p_wmax), s_pmax);
+  const ReadOffsets ro = make_read_offsets(lane);
+  WideLane ln;
+  ln.pA = cA.p_q;
+  ln.pB = cB.p_q;
+  ln.p_wminA = cA.p_wmin;
+  ln.p_wminB = cB.p_wmin;
+  ln.hf = hf;
+  ln.scale_log2 = scale_log2;
+
+  const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
+  const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
+  const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
+  const auto plan = make_dma_plan<NW>(kv_row_elems);
+
+  WaveState wA, wB;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      wA.O[dt][r] = 0.f;
+      wB.O[dt][r] = 0.f;
+    }
+  wA.m_run = wB.m_run = -INFINITY;
+  wA.l_run = wB.l_run = 0.f;
+
+  // Prologue: tiles 0 and 1 staged; S and softmax of half tile 0 and S of half tile 1 without overlap.
+  issue_tile_dma<NW>(plan, k_lds[0], v_lds[0], k_base, v_base, kv_row_elems, 0, n_kv);
+  issue_tile_dma<NW>(plan, k_lds[1], v_lds[1], k_base, v_base, kv_row_elems, 1, n_kv);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  issue_tile_dma<NW>(plan, k_lds[2], v_lds[2], k_base, v_base, kv_row_elems, 2, n_kv);
+
+  // S0/P0 belong to the first half of a tile, S1/P1 to the second.
+  f32x16 S0A, S0B, S1A, S1B;
+  PHalf P0A, P0B, P1A, P1B;
+  wide_qk(S0A, S0B, qA, qB, k_lds[0], 0, ro);
+  {
+    SoftmaxTmp tA, tB;
+#pragma unroll
+    for (int C = 0; C < 16; ++C) softmax_piece(C, S0A, wA, P0A, tA, 0, ln.pA, ln.p_wminA, hf, scale_log2);
+#pragma unroll
+    for (int C = 0; C < 16; ++C) softmax_piece(C, S0B, wB, P0B, tB, 0, ln.pB, ln.p_wminB, hf, scale_log2);
+    // O is still zero: the rescale of the first half tile has nothing to scale
+  }
+  wide_qk(S1A, S1B, qA, qB, k_lds[0], 1, ro);
+  // second half of tile 0: adds half 0, normalises half 1, multiplies the first half of tile 1
+  wide_step(wA, wB, qA, qB, P0A, P0B, P1A, P1B, S1A, S1B, S0A, S0B, v_lds[0], 0, k_lds[1], 0, ro, ln, 32);
+
+  for (int i = 1; i < n_tiles; ++i) {
+    // tile i+1 must have landed (requested one iteration earlier); the stage that held tile i-2 is
+    // free once every wavefront has passed the barrier
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    issue_tile_dma<NW>(plan, k_lds[(i + 2) & 3], v_lds[(i + 2) & 3], k_base, v_base, kv_row_elems, i + 2, n_kv);
+    // first half of tile i: adds the second half of tile i-1, multiplies the second half of tile i
+    wide_step(wA, wB, qA, qB, P1A, P1B, P0A, P0B, S0A, S0B, S1A, S1B, v_lds[(i - 1) & 3], 1, k_lds[i & 3], 1, ro, ln,
+              i * TK);
+    // second half of tile i: adds the first half of tile i, multiplies the first half of tile i+1
+    wide_step(wA, wB, qA, qB, P0A, P0B, P1A, P1B, S1A, S1B, S0A, S0B, v_lds[i & 3], 0, k_lds[(i + 1) & 3], 0, ro, ln,
+              i * TK + 32);
+  }
+  // Epilogue: second product of the last half tile.
+  wide_pv(wA, wB, P1A, P1B, v_lds[(n_tiles - 1) & 3], 1, ro);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is released
+  write_output(wA, cA, out, lse_out, n_q_heads, g, G, hf);
+  write_output(wB, cB, out, lse_out, n_q_heads, g, G, hf);
+}
+
 }  // namespace
 
 bool attention_mfma_supported(const ifkv_ctx *ctx) {
@@ -474,6 +766,18 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
   const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
+  {
+    const char *env = getenv("IFKV_ATTN_WIDE");  // tuning aid: same as the layer flag
+    if ((d.flags & IFKV_FLAG_ATTN_WIDE) || (env != nullptr && atoi(env) == 1)) {
+      const int rpbw = 256 / G;
+      dim3 gridw(d.n_kv_heads, static_cast<unsigned>((n_rows + rpbw - 1) / rpbw));
+      hipLaunchKernelGGL(attn_wide_kernel, gridw, dim3(256), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
+                         row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
+                         static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
+                         lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpbw);
+      return hipGetLastError();
+    }
+  }
   // IFKV_ATTN_WAVES=8 selects the 256-column variant (tuning aid).
   const int rpb8 = 256 / G;
   bool big = false;

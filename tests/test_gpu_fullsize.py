@@ -11,6 +11,7 @@ from tests.helpers import DEV, bf16_ulp, make_layer, score_tol, to_dev, to_host_
 from workloads import make_recompute_inputs, make_workload, preset, to_f64, to_storage
 
 pytestmark = pytest.mark.gpu
+ATTN_WIDE = 2  # layer flag: alternative stage-4 schedule
 
 
 def rng(seed):
@@ -127,6 +128,14 @@ def test_splice_and_attention_sampled_rows(run):
     got = to_host_f64(out, spec.dtype)[pick]
     assert np.abs(got - ref).max() <= 2e-2
     assert np.abs(lse.cpu().numpy().astype(np.float64)[pick] - lse_ref).max() <= 2e-2
+    # the alternative (one wavefront per SIMD) schedule of stage 4 on the same inputs
+    Lw = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=spec.m_prompt, flags=ATTN_WIDE)
+    out_w, lse_w = Lw.recompute_attention(to_dev(q_sel, spec.dtype), idx_d, K, V, return_lse=True)
+    torch.cuda.synchronize()
+    assert np.abs(to_host_f64(out_w, spec.dtype)[pick] - ref).max() <= 2e-2
+    assert np.abs(lse_w.cpu().numpy().astype(np.float64)[pick] - lse_ref).max() <= 2e-2
+    assert np.abs(to_host_f64(out_w, spec.dtype) - to_host_f64(out, spec.dtype)).max() <= 2e-2
+    Lw.close()
     # property at any size: outputs are convex combinations of V rows
     vmax = np.abs(V64).max()
     assert np.abs(to_host_f64(out, spec.dtype)).max() <= vmax * 1.01

@@ -20,6 +20,7 @@ from workloads import make_recompute_inputs, make_workload, preset, to_f64, to_s
 pytestmark = pytest.mark.gpu
 
 FORCE_GENERIC = 1
+ATTN_WIDE = 2
 
 
 def sync():
@@ -311,6 +312,12 @@ ATTN_CASES = [
     ("C5-gqa7", preset("C5", chunk_lens=[64] * 16 + [32] * 8, m_prompt=8), 192, 0),
     ("few-rows", preset("C2", chunk_lens=[500], m_prompt=8), 3, 0),
     ("many-rows-big-blocks", preset("C2", chunk_lens=[640] * 8, m_prompt=8), 4200, 0),
+    # the one-wavefront-per-SIMD schedule of the same stage
+    ("C2-ragged-wide", preset("C2", chunk_lens=[333, 120, 250], m_prompt=8), 105, ATTN_WIDE),
+    ("C3-small-wide", preset("C3", chunk_lens=[100] * 11, m_prompt=8), 165, ATTN_WIDE),
+    ("C5-gqa7-wide", preset("C5", chunk_lens=[64] * 16 + [32] * 8, m_prompt=8), 192, ATTN_WIDE),
+    ("few-rows-wide", preset("C2", chunk_lens=[500], m_prompt=8), 3, ATTN_WIDE),
+    ("many-rows-wide", preset("C2", chunk_lens=[640] * 8, m_prompt=8), 4200, ATTN_WIDE),
 ]
 
 
@@ -318,22 +325,22 @@ ATTN_CASES = [
 def test_attention_parity_bf16(name, spec, k, flags):
     n_ctx = int(np.sum(spec.chunk_lens)) if spec.chunk_lens is not None else make_workload(spec).n_ctx
     rows = sample_rows(n_ctx, min(k, n_ctx), 2)
-    if name == "many-rows-big-blocks":
+    if name.startswith("many-rows"):
         # the oracle checks a subsample of rows (rows are independent)
-        out, lse, ref, lse_ref = attention_case_subsampled(spec, rows, 300)
+        out, lse, ref, lse_ref = attention_case_subsampled(spec, rows, 300, flags=flags)
     else:
         out, lse, ref, lse_ref = attention_case(spec, rows, flags=flags)
     assert np.abs(out - ref).max() <= 2e-2, np.abs(out - ref).max()
     assert np.abs(lse - lse_ref).max() <= 2e-2
 
 
-def attention_case_subsampled(spec, rows, n_check):
+def attention_case_subsampled(spec, rows, n_check, flags=0):
     wl = make_workload(spec)
     K_st, K64, _ = global_keys(wl)
     V_st = np.concatenate([wl.v_chunks[c] for c in wl.chunk_order], axis=0)
     V64 = to_f64(V_st, spec.dtype)
     q_sel, _, _ = make_recompute_inputs(wl, rows)
-    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8, flags=flags)
     out, lse = L.recompute_attention(to_dev(q_sel, spec.dtype), torch.from_numpy(rows.astype(np.int32)).to(DEV),
                                      to_dev(K_st, spec.dtype), to_dev(V_st, spec.dtype), return_lse=True)
     sync()
@@ -344,23 +351,26 @@ def attention_case_subsampled(spec, rows, n_check):
     return to_host_f64(out, spec.dtype)[pick], lse.cpu().numpy().astype(np.float64)[pick], ref, lse_ref
 
 
-def test_attention_full_ratio_is_dense_causal():
+@pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
+def test_attention_full_ratio_is_dense_causal(flags):
     spec = preset("C2", chunk_lens=[150, 83], m_prompt=8)
-    out, lse, ref, lse_ref = attention_case(spec, np.arange(233))
+    out, lse, ref, lse_ref = attention_case(spec, np.arange(233), flags=flags)
     assert np.abs(out - ref).max() <= 2e-2
     # first row attends to itself only: output is V[0] up to the bf16 rounding of P = 1
     assert np.abs(lse - lse_ref).max() <= 2e-2
 
 
-def test_attention_peaky_logits():
+@pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
+def test_attention_peaky_logits(flags):
     spec = preset("C2", chunk_lens=[700, 301], m_prompt=8, sigma=0.3)
     rows = sample_rows(1001, 150, 4)
-    out, lse, ref, lse_ref = attention_case(spec, rows, q_gain=6.0)
+    out, lse, ref, lse_ref = attention_case(spec, rows, q_gain=6.0, flags=flags)
     assert np.abs(out - ref).max() <= 2e-2
     assert np.abs(lse - lse_ref).max() <= 2e-2
 
 
-def test_attention_out_of_range_rows_give_zeros():
+@pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
+def test_attention_out_of_range_rows_give_zeros(flags):
     spec = preset("C2", chunk_lens=[128], m_prompt=8)
     wl = make_workload(spec)
     K_st, K64, _ = global_keys(wl)
@@ -368,7 +378,7 @@ def test_attention_out_of_range_rows_give_zeros():
     rows = np.array([5, 60, 127], dtype=np.int64)
     q_sel, _, _ = make_recompute_inputs(wl, rows)
     bad = torch.tensor([5, 128, -1], dtype=torch.int32, device=DEV)
-    L = make_layer(spec, max_ctx=128, max_prompt=8)
+    L = make_layer(spec, max_ctx=128, max_prompt=8, flags=flags)
     out = L.recompute_attention(to_dev(q_sel, "bf16"), bad, to_dev(K_st, "bf16"), to_dev(V_st, "bf16"))
     sync()
     o = to_host_f64(out, "bf16")
