@@ -227,6 +227,60 @@ def splice_kv(k_cache: np.ndarray, v_cache: np.ndarray, k_new: np.ndarray,
 # ---------------------------------------------------------------------------
 # Composite
 # ---------------------------------------------------------------------------
+# ---------------------------------------------------------------------------
+# Chunk reordering (optional step before the path, "Chunk Reordering")
+# ---------------------------------------------------------------------------
+def chunk_selection_counts(idx: np.ndarray, chunk_len: Sequence[int],
+                           chunk_order: Optional[Sequence[int]]) -> np.ndarray:
+    """Numerator of Eq. (9): |S ∩ C_i| for every chunk i, where idx holds the
+    selected global row indices and chunk i occupies rows
+    [Delta_i, Delta_i + len_i) of the concatenation.  Returned per chunk id."""
+    start, _ = chunk_starts(chunk_len, chunk_order)
+    counts = np.zeros(len(chunk_len), dtype=np.int64)
+    for i in range(len(chunk_len)):
+        lo, hi = int(start[i]), int(start[i]) + int(chunk_len[i])
+        counts[i] = sum(1 for j in np.asarray(idx).tolist() if lo <= j < hi)
+    return counts
+
+
+def reorder_chunks(chunk_len: Sequence[int], chunk_order: Optional[Sequence[int]],
+                   counts: Sequence[int]) -> np.ndarray:
+    """"Chunk Reordering": chunks with a larger density r_i = |S ∩ C_i| / |C_i|
+    (Eq. 9) are placed closer to the prompt, i.e. later in the concatenation;
+    chunks with equal r_i keep their current relative order.  Reading where the
+    paper is silent: an empty chunk has r_i = 0; densities are compared exactly
+    (as fractions), so equality means equality.
+
+    Returns the new slot -> chunk order."""
+    from fractions import Fraction
+    n = len(chunk_len)
+    order = list(range(n)) if chunk_order is None else [int(c) for c in chunk_order]
+    dens = [Fraction(int(counts[c]), int(chunk_len[c])) if int(chunk_len[c]) > 0 else Fraction(0) for c in range(n)]
+    # insertion sort on the current order, ascending density: stable by construction
+    out: List[int] = []
+    for c in order:
+        pos = len(out)
+        while pos > 0 and dens[out[pos - 1]] > dens[c]:
+            pos -= 1
+        out.insert(pos, c)
+    return np.asarray(out, dtype=np.int64)
+
+
+def reorder_pass(k_chunks, chunk_len, chunk_order, theta, pairing, q_prompt, sm_scale, ratio):
+    """First-stage selection of "Chunk Reordering" with the local-context
+    geometry the paper uses for it (appendix "RoPE Geometry", last paragraph):
+    every chunk keeps its chunk-local rotary positions (phase advance 0), the
+    prompt stays at its global position; one global top-k over the scores;
+    Eq. (9) per chunk; new order.  Returns (new_order, counts, idx)."""
+    n = len(chunk_len)
+    K, _, _, N = reposition_keys(k_chunks, None, chunk_len, chunk_order, theta, pairing,
+                                 delta_override=[0] * n)
+    s = score_tokens(K, q_prompt, sm_scale)
+    idx = select_topk(s, budget(N, ratio))
+    counts = chunk_selection_counts(idx, chunk_len, chunk_order)
+    return reorder_chunks(chunk_len, chunk_order, counts), counts, idx
+
+
 def recompute_layer(k_chunks, v_chunks, chunk_len, chunk_order, theta, pairing,
                     q_prompt, sm_scale, ratio, make_rows):
     """One layer of the path in the paper's order: assemble and re-rotate,

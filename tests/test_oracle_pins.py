@@ -411,3 +411,80 @@ def test_recompute_inputs_shapes_and_rope():
     idx = np.array([0, 5, 31])
     q, kn, vn = make_recompute_inputs(wl, idx)
     assert q.shape == (3, 32, 128) and kn.shape == (3, 8, 128) and vn.dtype == np.uint16
+
+
+# --------------------------------------------------------------------------
+# chunk reordering (Eq. 9)
+# --------------------------------------------------------------------------
+def test_chunk_counts_bruteforce_and_hand_case():
+    # hand case: chunks of 3, 2, 4 rows in order [2, 0, 1] -> chunk 2 rows 0..3, chunk 0 rows 4..6, chunk 1 rows 7..8
+    lens, order = [3, 2, 4], [2, 0, 1]
+    idx = np.array([0, 3, 4, 8])
+    assert O.chunk_selection_counts(idx, lens, order).tolist() == [1, 1, 2]
+    g = rng(31)
+    for _ in range(20):
+        n = int(g.integers(1, 7))
+        lens = g.integers(0, 9, size=n).tolist()
+        order = g.permutation(n).tolist()
+        N = sum(lens)
+        k = int(g.integers(0, N + 1))
+        idx = np.sort(g.choice(N, size=k, replace=False)) if N else np.array([], dtype=np.int64)
+        # independent side: label every row with its chunk, then count labels
+        owner = []
+        for c in order:
+            owner += [c] * lens[c]
+        want = [sum(1 for j in idx.tolist() if owner[j] == c) for c in range(n)]
+        assert O.chunk_selection_counts(idx, lens, order).tolist() == want
+        assert sum(want) == k
+
+
+def test_reorder_is_stable_ascending_density():
+    # densities 2/4, 1/2 (equal), 0/3, 3/3: ascending; the two equal ones keep their current relative order
+    lens, counts = [4, 2, 3, 3], [2, 1, 0, 3]
+    assert O.reorder_chunks(lens, [0, 1, 2, 3], counts).tolist() == [2, 0, 1, 3]
+    assert O.reorder_chunks(lens, [1, 0, 3, 2], counts).tolist() == [2, 1, 0, 3]
+    # densest chunk ends next to the prompt (last slot); all-equal densities change nothing
+    assert O.reorder_chunks([5, 5, 5], [2, 0, 1], [1, 1, 1]).tolist() == [2, 0, 1]
+    # empty chunk counts as density 0
+    assert O.reorder_chunks([0, 4, 4], None, [0, 1, 2]).tolist() == [0, 1, 2]
+    assert O.reorder_chunks([4, 0, 4], None, [2, 0, 1]).tolist() == [1, 2, 0]
+    # against Python's stable sort on exact fractions
+    from fractions import Fraction
+    g = rng(32)
+    for _ in range(50):
+        n = int(g.integers(1, 9))
+        lens = g.integers(1, 6, size=n).tolist()
+        counts = [int(g.integers(0, L + 1)) for L in lens]
+        order = g.permutation(n).tolist()
+        want = sorted(order, key=lambda c: Fraction(counts[c], lens[c]))
+        assert O.reorder_chunks(lens, order, counts).tolist() == want
+
+
+def test_reorder_pass_is_local_geometry_then_density_sort():
+    """The first pass scores the chunks' keys exactly as cached (chunk-local rotary positions: the
+    concatenation of the chunk caches, no rotation) against the prompt at its global position,
+    takes one global top-k, and sorts the chunks by Eq. (9).  Every step is redone here with
+    independent pieces: numpy concatenation, the brute-force scores, a sort on (-score, index),
+    row labels and Python's stable sort on exact fractions."""
+    from fractions import Fraction
+    spec = preset("C1", chunk_lens=[9, 14, 5, 11], m_prompt=3, permute_order=True, n_q_heads=2, n_kv_heads=1,
+                  head_dim=8, planted_count=4)
+    wl = make_workload(spec)
+    kc = [to_f64(c, spec.dtype) for c in wl.k_chunks]
+    q = to_f64(wl.q_prompt, spec.dtype)
+    ratio = 0.3
+    new_order, counts, idx = O.reorder_pass(kc, wl.chunk_len, wl.chunk_order, spec.rope_theta, spec.pairing, q,
+                                            wl.sm_scale, ratio)
+    order = [int(c) for c in wl.chunk_order]
+    K_local = np.concatenate([kc[c] for c in order], axis=0)
+    s = brute_scores(K_local, q, wl.sm_scale, 2)
+    k = int(math.floor(ratio * K_local.shape[0]))
+    want_idx = sorted(sorted(range(len(s)), key=lambda j: (-s[j], j))[:k])
+    assert idx.tolist() == want_idx
+    owner = []
+    for c in order:
+        owner += [c] * int(wl.chunk_len[c])
+    want_counts = [sum(1 for j in want_idx if owner[j] == c) for c in range(4)]
+    assert counts.tolist() == want_counts
+    want_order = sorted(order, key=lambda c: Fraction(want_counts[c], int(wl.chunk_len[c])))
+    assert new_order.tolist() == want_order
