@@ -14,6 +14,9 @@
  *                             full prefix
  *   ifkv_splice_kv            write the recomputed K/V rows back into the cache
  *
+ * and, where the chunks are exchangeable, ifkv_chunk_counts + ifkv_reorder_chunks
+ * derive a better chunk order from a first-stage selection.
+ *
  * General conventions
  * -------------------
  * - Every tensor is dense, row-major, [tokens, heads, head_dim], in the dtype of
@@ -236,6 +239,44 @@ int ifkv_recompute_attention(ifkv_ctx *ctx, const void *q_sel,
 int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new,
                    const int32_t *idx, int64_t n_rows,
                    void *k_cache, void *v_cache, int64_t n_kv);
+
+/*
+ * Optional step before the path -- Method, "Chunk Reordering", Eq. (9).
+ *
+ * After a first-stage selection (stages 1-3 run with the local-context
+ * geometry: delta_override all 0, prompt queries at their global positions),
+ * chunk i's importance is the density r_i = |S ∩ C_i| / |C_i| of selected
+ * tokens in it.  ifkv_chunk_counts computes the numerators on the device from
+ * the selected set; ifkv_reorder_chunks (host only, no GPU call) turns them
+ * into the new order: ascending r_i, so the densest chunk ends up next to the
+ * prompt, and chunks with equal r_i keep their relative order.  Densities are
+ * compared exactly (count_a * len_b against count_b * len_a); an empty chunk
+ * has density 0.  The caller then runs the path again with the new order.
+ *
+ *   idx          device int32 [k], ascending (as ifkv_select_topk writes it)
+ *   n_slots      number of chunk slots in the concatenation idx refers to
+ *   slot_start   host, n_slots entries: first row of each slot, ascending
+ *                (chunk_start_out of stage 1 gathered by chunk_order)
+ *   n_ctx        total rows; slot s covers [slot_start[s], slot_start[s+1]) and
+ *                the last slot ends at n_ctx
+ *   counts_out   device int32 [n_slots]: selected rows per slot
+ * Errors: IFKV_EINVAL for NULL pointers, negative sizes, slot_start not
+ * ascending within [0, n_ctx].
+ */
+int ifkv_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, int32_t n_slots,
+                      const int64_t *slot_start, int64_t n_ctx, int32_t *counts_out);
+
+/*
+ *   n_chunks     number of chunks
+ *   order_in     host, slot -> chunk id of the order the counts refer to; NULL = identity
+ *   slot_counts  host, n_chunks entries: selected rows per SLOT (ifkv_chunk_counts copied back)
+ *   chunk_len    host, n_chunks entries indexed by chunk id
+ *   order_out    host, n_chunks entries: the new slot -> chunk id order
+ * Errors: IFKV_EINVAL for NULL pointers, order_in not a permutation, a count
+ * that is negative or exceeds its chunk's length.  ctx may be NULL.
+ */
+int ifkv_reorder_chunks(ifkv_ctx *ctx, int32_t n_chunks, const int32_t *order_in, const int32_t *slot_counts,
+                        const int32_t *chunk_len, int32_t *order_out);
 
 /*
  * Calibration utility (not part of the method): a plain streaming copy of

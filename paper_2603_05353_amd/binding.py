@@ -26,7 +26,8 @@ IFKV_FLAG_ATTN_WIDE = 2
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
     "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
-    "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_copy_bytes",
+    "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_chunk_counts", "ifkv_reorder_chunks",
+    "ifkv_copy_bytes",
 )
 
 
@@ -79,6 +80,10 @@ def load_library() -> C.CDLL:
     lib.ifkv_recompute_attention.restype = C.c_int
     lib.ifkv_splice_kv.argtypes = [vp, vp, vp, vp, i64, vp, vp, i64]
     lib.ifkv_splice_kv.restype = C.c_int
+    lib.ifkv_chunk_counts.argtypes = [vp, vp, i64, i32, C.POINTER(i64), i64, vp]
+    lib.ifkv_chunk_counts.restype = C.c_int
+    lib.ifkv_reorder_chunks.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+    lib.ifkv_reorder_chunks.restype = C.c_int
     lib.ifkv_copy_bytes.argtypes = [vp, vp, vp, i64]
     lib.ifkv_copy_bytes.restype = C.c_int
     _lib = lib
@@ -215,6 +220,23 @@ class Layer:
                   k_cache: torch.Tensor, v_cache: Optional[torch.Tensor]) -> None:
         self._check(self._lib.ifkv_splice_kv(self._ctx, _ptr(k_new), _ptr(v_new), _ptr(idx), int(idx.shape[0]),
                                              _ptr(k_cache), _ptr(v_cache), int(k_cache.shape[0])))
+
+    def chunk_counts(self, idx: torch.Tensor, slot_start: Sequence[int], n_ctx: int,
+                     counts_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n_slots = len(slot_start)
+        if counts_out is None:
+            counts_out = self._empty(max(n_slots, 1), dtype=torch.int32)
+        self._check(self._lib.ifkv_chunk_counts(self._ctx, _ptr(idx), int(idx.shape[0]), n_slots,
+                                                _i64_array(slot_start), int(n_ctx), _ptr(counts_out)))
+        return counts_out[:n_slots]
+
+    def reorder_chunks(self, order_in: Optional[Sequence[int]], slot_counts: Sequence[int],
+                       chunk_len: Sequence[int]) -> List[int]:
+        n = len(chunk_len)
+        out = (C.c_int32 * max(n, 1))()
+        self._check(self._lib.ifkv_reorder_chunks(self._ctx, n, _i32_array(order_in), _i32_array(slot_counts),
+                                                  _i32_array(chunk_len), out))
+        return [int(out[i]) for i in range(n)]
 
     def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor) -> None:
         self._check(self._lib.ifkv_copy_bytes(self._ctx, _ptr(dst), _ptr(src), src.numel() * src.element_size()))

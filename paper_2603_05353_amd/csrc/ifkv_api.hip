@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/ifkv.h: argument validation
 // (before any GPU call), host-side bookkeeping (chunk starts, budget), scratch
 // management and dispatch to the stage launchers.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -289,6 +290,62 @@ int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new, const in
     return fail(ctx, IFKV_EINVAL, "splice_kv: tensors must be 16-byte aligned");
   hipError_t e = ifkv::launch_splice(ctx, k_new, v_new, idx, n_rows, k_cache, v_cache, n_kv);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "splice kernel launch");
+}
+
+int ifkv_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, int32_t n_slots, const int64_t *slot_start,
+                      int64_t n_ctx, int32_t *counts_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (k < 0 || n_slots < 0 || n_ctx < 0) return fail(ctx, IFKV_EINVAL, "chunk_counts: negative size");
+  if (n_ctx > ctx->desc.max_ctx || k > n_ctx)
+    return fail(ctx, IFKV_ESHAPE, "chunk_counts: n_ctx=%lld (k=%lld) exceeds max_ctx=%lld",
+                static_cast<long long>(n_ctx), static_cast<long long>(k), static_cast<long long>(ctx->desc.max_ctx));
+  if (n_slots == 0) return IFKV_OK;
+  if (slot_start == nullptr || counts_out == nullptr || (k > 0 && idx == nullptr))
+    return fail(ctx, IFKV_EINVAL, "chunk_counts: NULL pointer");
+  for (int32_t s = 0; s < n_slots; ++s) {
+    const int64_t lo = slot_start[s], hi = s + 1 < n_slots ? slot_start[s + 1] : n_ctx;
+    if (lo < 0 || lo > hi || hi > n_ctx)
+      return fail(ctx, IFKV_EINVAL, "chunk_counts: slot_start must ascend within [0, n_ctx] (slot %d)", s);
+  }
+  // boundaries travel in the kernel arguments, kRepoMaxChunks slots per launch
+  for (int32_t s0 = 0; s0 < n_slots; s0 += ifkv::kRepoMaxChunks) {
+    ifkv::SlotBounds b;
+    b.n = n_slots - s0 < ifkv::kRepoMaxChunks ? n_slots - s0 : ifkv::kRepoMaxChunks;
+    for (int32_t t = 0; t <= b.n; ++t)
+      b.bound[t] = static_cast<int32_t>(s0 + t < n_slots ? slot_start[s0 + t] : n_ctx);
+    hipError_t e = ifkv::launch_chunk_counts(ctx, idx, k, b, counts_out + s0);
+    if (e != hipSuccess) return hip_fail(ctx, e, "chunk_counts kernel launch");
+  }
+  return IFKV_OK;
+}
+
+int ifkv_reorder_chunks(ifkv_ctx *ctx, int32_t n_chunks, const int32_t *order_in, const int32_t *slot_counts,
+                        const int32_t *chunk_len, int32_t *order_out) {
+  if (n_chunks < 0) return fail(ctx, IFKV_EINVAL, "reorder_chunks: negative chunk count");
+  if (n_chunks == 0) return IFKV_OK;
+  if (slot_counts == nullptr || chunk_len == nullptr || order_out == nullptr)
+    return fail(ctx, IFKV_EINVAL, "reorder_chunks: NULL pointer");
+  std::vector<int32_t> order(n_chunks);
+  std::vector<char> seen(n_chunks, 0);
+  for (int32_t s = 0; s < n_chunks; ++s) {
+    const int32_t c = order_in != nullptr ? order_in[s] : s;
+    if (c < 0 || c >= n_chunks || seen[c]) return fail(ctx, IFKV_EINVAL, "reorder_chunks: order_in is not a permutation");
+    seen[c] = 1;
+    order[s] = c;
+    if (chunk_len[c] < 0 || slot_counts[s] < 0 || slot_counts[s] > chunk_len[c])
+      return fail(ctx, IFKV_EINVAL, "reorder_chunks: slot %d has count %d for a chunk of %d rows", s, slot_counts[s],
+                  chunk_len[c]);
+  }
+  // Eq. (9) compared exactly: r_a < r_b  <=>  count_a * len_b < count_b * len_a (empty chunk: r = 0)
+  std::vector<int32_t> slot(n_chunks);
+  for (int32_t s = 0; s < n_chunks; ++s) slot[s] = s;
+  std::stable_sort(slot.begin(), slot.end(), [&](int32_t a, int32_t b) {
+    const int64_t la = chunk_len[order[a]], lb = chunk_len[order[b]];
+    const int64_t ca = la > 0 ? slot_counts[a] : 0, cb = lb > 0 ? slot_counts[b] : 0;
+    return ca * (lb > 0 ? lb : 1) < cb * (la > 0 ? la : 1);
+  });
+  for (int32_t s = 0; s < n_chunks; ++s) order_out[s] = order[slot[s]];
+  return IFKV_OK;
 }
 
 int ifkv_copy_bytes(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes) {

@@ -62,6 +62,13 @@ hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row
                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                             float *lse_out);
 
+// Chunk reordering: selected rows per slot.  At most kRepoMaxChunks boundaries per launch.
+struct SlotBounds {
+  int32_t bound[kRepoMaxChunks + 1];  // bound[s] .. bound[s+1]: rows of slot s
+  int32_t n;                          // slots in this launch
+};
+hipError_t launch_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, const SlotBounds &b, int32_t *counts_out);
+
 // Stage 5.
 hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, const int32_t *idx,
                          int64_t n_rows, void *k_cache, void *v_cache, int64_t n_kv);

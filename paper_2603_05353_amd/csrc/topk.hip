@@ -324,7 +324,36 @@ __global__ __launch_bounds__(kStreamThreads) void topk_streaming_kernel(const fl
   }
 }
 
+// "Chunk Reordering", Eq. (9), numerator: idx is ascending, so the rows of slot s are the
+// index range [lower_bound(bound[s]), lower_bound(bound[s+1])).  One thread per boundary.
+__global__ __launch_bounds__(128) void chunk_counts_kernel(const int32_t *__restrict__ idx, int k, SlotBounds b,
+                                                           int32_t *__restrict__ counts_out) {
+  __shared__ int pos[kRepoMaxChunks + 1];
+  const int t = threadIdx.x;
+  if (t <= b.n) {
+    const int target = b.bound[t];
+    int lo = 0, hi = k;  // first position whose index is >= target
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (idx[mid] < target)
+        lo = mid + 1;
+      else
+        hi = mid;
+    }
+    pos[t] = lo;
+  }
+  __syncthreads();
+  if (t < b.n) counts_out[t] = pos[t + 1] - pos[t];
+}
+
 }  // namespace
+
+hipError_t launch_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, const SlotBounds &b,
+                               int32_t *counts_out) {
+  if (b.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(chunk_counts_kernel, dim3(1), dim3(128), 0, ctx->stream, idx, static_cast<int>(k), b, counts_out);
+  return hipGetLastError();
+}
 
 size_t topk_scratch_bytes(const ifkv_ctx *, int64_t) { return 0; }
 

@@ -146,3 +146,42 @@ def test_product_does_not_import_oracle():
                 assert "oracle" not in text.lower(), fn
     with open(os.path.join(ROOT, "oracle", "infoflow_oracle.py")) as f:
         assert "paper_2603_05353_amd" not in f.read().replace("from the product", "")
+
+
+# --------------------------------------------------------------------------
+# chunk reordering: the order computation is host-only, so it is checked against the oracle here
+# --------------------------------------------------------------------------
+def test_reorder_chunks_matches_oracle(lib):
+    import numpy as np
+    from oracle import infoflow_oracle as O
+    g = np.random.Generator(np.random.Philox(key=[41, 7]))
+    L = _layer()
+    for _ in range(200):
+        n = int(g.integers(1, 12))
+        lens = g.integers(0, 7, size=n).tolist()
+        order = g.permutation(n).tolist()
+        counts_by_chunk = [int(g.integers(0, lens[c] + 1)) for c in range(n)]
+        slot_counts = [counts_by_chunk[c] for c in order]
+        got = L.reorder_chunks(order, slot_counts, lens)
+        assert got == O.reorder_chunks(lens, order, counts_by_chunk).tolist()
+    # identity order when order_in is NULL; equal densities keep their order
+    assert L.reorder_chunks(None, [1, 2, 3], [2, 4, 6]) == [0, 1, 2]
+    assert L.reorder_chunks(None, [3, 0, 1], [3, 3, 3]) == [1, 2, 0]
+    L.close()
+
+
+def test_reorder_and_counts_reject_bad_arguments(lib):
+    L = _layer()
+    for order, counts, lens in [([0, 0], [0, 0], [1, 1]), ([0, 2], [0, 0], [1, 1]), (None, [2, 0], [1, 1]),
+                                (None, [-1, 0], [1, 1])]:
+        with pytest.raises(B.IfkvError) as e:
+            L.reorder_chunks(order, counts, lens)
+        assert e.value.code == B.IFKV_EINVAL
+    # slot starts must ascend within [0, n_ctx]; checked on the host before any GPU call
+    arr = (C.c_int64 * 2)(5, 3)
+    out = (C.c_int32 * 2)()
+    rc = lib.ifkv_chunk_counts(L._ctx, None, 0, 2, arr, 10, C.cast(out, C.c_void_p))
+    assert rc == B.IFKV_EINVAL and b"ascend" in lib.ifkv_last_error(L._ctx)
+    rc = lib.ifkv_chunk_counts(L._ctx, None, 0, 2, None, 10, C.cast(out, C.c_void_p))
+    assert rc == B.IFKV_EINVAL
+    L.close()

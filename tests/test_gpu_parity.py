@@ -469,3 +469,72 @@ def test_composite_layer(cfg, rtol_sel):
     tol = 1e-4 if spec.dtype == "f32" else 2e-2
     assert np.abs(to_host_f64(out, spec.dtype) - ref).max() <= tol
     L.close()
+
+
+# ---------------------------------------------------------------------------
+# chunk reordering
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n_slots,n_ctx,k", [(1, 100, 30), (4, 1024, 153), (64, 32768, 4915), (100, 5000, 700),
+                                              (7, 50, 0), (5, 40, 40)])
+def test_chunk_counts_bit_exact(n_slots, n_ctx, k):
+    g = np.random.Generator(np.random.Philox(key=[n_slots, n_ctx]))
+    cuts = np.sort(g.choice(n_ctx + 1, size=n_slots - 1, replace=True)) if n_slots > 1 else np.array([], dtype=np.int64)
+    starts = np.concatenate([[0], cuts]).astype(np.int64)           # empty slots allowed
+    lens = np.diff(np.concatenate([starts, [n_ctx]])).astype(np.int64)
+    idx = np.sort(g.choice(n_ctx, size=k, replace=False)).astype(np.int32)
+    spec = preset("C2", chunk_lens=[int(n_ctx)], m_prompt=8)
+    L = make_layer(spec, max_ctx=n_ctx, max_prompt=8)
+    got = L.chunk_counts(torch.from_numpy(idx).to(DEV), starts.tolist(), n_ctx)
+    sync()
+    want = O.chunk_selection_counts(idx.astype(np.int64), lens.tolist(), None)   # slots in identity order
+    assert np.array_equal(got.cpu().numpy().astype(np.int64), want)
+    L.close()
+
+
+def test_reorder_two_pass_flow():
+    """First-stage selection under the local geometry, Eq. (9), new order, second pass under the
+    GLOBAL geometry of the new order -- GPU against oracle at every hand-over."""
+    spec = preset("C2", chunk_lens=[200, 96, 310, 128, 64, 226], m_prompt=24, permute_order=True)
+    wl = make_workload(spec)
+    k, v, q = oracle_inputs(wl)
+    ratio = 0.15
+    n = len(wl.chunk_len)
+    order = wl.chunk_order.tolist()
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=spec.m_prompt)
+    kd, vd = dev_chunks(wl)
+    qd = to_dev(wl.q_prompt, spec.dtype)
+    # pass 1 on the GPU: phase advance 0 for every chunk
+    K1, _, starts, N = L.reposition_keys(kd, None, chunk_order=order, delta_override=[0] * n)
+    s1 = L.score_tokens(K1, qd)
+    idx1 = L.select_topk(s1, ratio=ratio)
+    slot_start = [starts[c] for c in order]
+    counts = L.chunk_counts(idx1, slot_start, N)
+    sync()
+    # the keys of pass 1 are the cached keys, bit for bit
+    assert np.array_equal(to_host_bits(K1, spec.dtype), np.concatenate([wl.k_chunks[c] for c in order], axis=0))
+    # counts: exact for the GPU's own selection
+    idx1_h = idx1.cpu().numpy().astype(np.int64)
+    counts_h = counts.cpu().numpy().astype(np.int64)
+    want_counts = O.chunk_selection_counts(idx1_h, wl.chunk_len, order)       # per chunk id
+    assert np.array_equal(counts_h, want_counts[order])
+    new_order = L.reorder_chunks(order, counts_h.tolist(), wl.chunk_len.tolist())
+    assert new_order == O.reorder_chunks(wl.chunk_len, order, want_counts).tolist()
+    # the oracle's own first pass: selections may differ only near the threshold, so per-chunk counts
+    # differ by at most the number of such tokens
+    ref_order, ref_counts, ref_idx = O.reorder_pass(k, wl.chunk_len, order, spec.rope_theta, spec.pairing, q,
+                                                    wl.sm_scale, ratio)
+    assert np.abs(ref_counts - want_counts).sum() <= 2 * len(np.setxor1d(ref_idx, idx1_h)) <= 8
+    if np.array_equal(ref_counts, want_counts):
+        assert new_order == ref_order.tolist()
+    # pass 2: the normal path on the new order
+    K2, V2, starts2, N2 = L.reposition_keys(kd, vd, chunk_order=new_order)
+    s2 = L.score_tokens(K2, qd)
+    idx2 = L.select_topk(s2, ratio=ratio)
+    sync()
+    Kref, _, start_ref, _ = O.reposition_keys(k, v, wl.chunk_len, new_order, spec.rope_theta, spec.pairing)
+    assert starts2 == start_ref.tolist() and N2 == N
+    s_ref = O.score_tokens(Kref, q, wl.sm_scale)
+    s2_h = s2.cpu().numpy().astype(np.float64)
+    assert (np.abs(s2_h - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all()
+    assert np.array_equal(idx2.cpu().numpy().astype(np.int64), O.select_topk(s2.cpu().numpy(), O.budget(N, ratio)))
+    L.close()
