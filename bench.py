@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-iters", type=int, default=20)
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="profiling aid for --only recompute_attention: all-zero K, V and queries (same instruction "
+                         "stream, least switching activity: shows how far the clock drops on real data)")
     ap.add_argument("--only", default=None,
                     choices=["reposition_keys", "score_tokens", "select_topk", "splice_kv",
                              "recompute_attention", "copy"],
@@ -110,6 +113,8 @@ def main():
     idx_k = idx[:k_sel]
 
     if args.only is not None:
+        if args.zero_inputs:
+            K.zero_(), V.zero_(), q_sel_d.zero_()
         src = torch.empty(2 * N * spec.n_kv_heads * spec.head_dim * e, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         fn = {
