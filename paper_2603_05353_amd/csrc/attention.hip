@@ -133,7 +133,10 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos,
 
 }  // namespace
 
-size_t attention_scratch_bytes(const ifkv_ctx *, int64_t, int64_t) { return 0; }
+size_t attention_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
+  const bool generic = (ctx->desc.flags & IFKV_FLAG_FORCE_GENERIC) || !attention_mfma_supported(ctx);
+  return generic ? 0 : attention_mfma_scratch_bytes(ctx, n_rows, n_kv);
+}
 
 hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out, float *lse_out) {

@@ -6,6 +6,8 @@
 namespace ifkv {
 
 bool attention_mfma_supported(const ifkv_ctx *ctx);
+// Scratch the MFMA path needs for the partial results of a launch split over the kv axis (0 if not split).
+size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv);
 hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                                  const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                                  float *lse_out);

@@ -27,8 +27,8 @@
 //
 // attn_mfma_kernel<4, 2>: 128 query columns per block, two LDS stages (64 KiB), two blocks per CU --
 // the default.  The two wavefronts that share a SIMD then belong to different blocks and are not
-// tied together by barriers.  attn_mfma_kernel<8, 3>: 256 query columns, three stages (96 KiB), one
-// block per CU; half the K/V traffic per flop, measured within 2 % of the default.
+// tied together by barriers.  (An 8-wavefront, three-stage instantiation with 256 query columns and
+// half the K/V traffic per flop measured within 2 % of it and is not built.)
 #include <cstdlib>
 
 #include "attention_common.h"
@@ -390,6 +390,73 @@ __device__ __forceinline__ int block_tiles(int p_wmax, int *s_pmax) {
 }
 
 // ---------------------------------------------------------------------------
+// Split over the kv axis.  Row blocks differ in length by two orders of magnitude (a row at
+// position p costs p keys), and a launch has only a few blocks per CU, so the longest blocks set
+// the finish time.  With `part_tiles` < the tile count of a row block, the block's kv range is
+// divided into parts of part_tiles tiles, one workgroup each (blockIdx.z); each part keeps its own
+// running (max, sum) and unnormalised O and writes them to scratch, and attn_combine_kernel merges
+// the parts of every row that was split.  Row blocks that fit in one part write their output
+// directly, as without the split.
+// ---------------------------------------------------------------------------
+struct SplitPlan {
+  int part_tiles;     // kv tiles per part (>= number of tiles of the cache: no split)
+  float *o_part;      // [parts][n_rows][H_q][D] unnormalised O
+  float2 *ml_part;    // [parts][n_rows][H_q] (reference max in the log2 domain, sum)
+  int *block_tiles;   // [row blocks] tile count of each row block (written by part 0)
+};
+
+__device__ __forceinline__ void write_partial(const WaveState &w, const Column &c, const SplitPlan &sp, int part,
+                                              int n_rows, int n_q_heads, int g, int G, int hf) {
+  if (!c.col_valid) return;
+  const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
+  const int64_t slot = (static_cast<int64_t>(part) * n_rows + c.row) * n_q_heads + g * G + c.hh;
+  float *orow = sp.o_part + slot * D;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int ri = 0; ri < 4; ++ri) {
+      float4 x = make_float4(w.O[dt][4 * ri + 0], w.O[dt][4 * ri + 1], w.O[dt][4 * ri + 2], w.O[dt][4 * ri + 3]);
+      *reinterpret_cast<float4 *>(orow + 32 * dt + 8 * ri + 4 * hf) = x;
+    }
+  if (hf == 0) sp.ml_part[slot] = make_float2(w.m_run, l_tot);
+}
+
+// One wavefront per (row, head) of a split row block: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+__global__ __launch_bounds__(256) void attn_combine_kernel(SplitPlan sp, const int32_t *__restrict__ row_pos,
+                                                           int n_rows, int n_kv, int n_q_heads, int rows_per_block,
+                                                           uint16_t *__restrict__ out, float *__restrict__ lse_out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int row = static_cast<int>(item / n_q_heads), head = static_cast<int>(item - static_cast<int64_t>(row) * n_q_heads);
+  if (row >= n_rows) return;
+  const int n_tiles = sp.block_tiles[row / rows_per_block];
+  const int n_parts = (n_tiles + sp.part_tiles - 1) / sp.part_tiles;
+  if (n_parts <= 1) return;  // written directly by the attention kernel
+  const int p = row_pos[row];
+  const bool in_range = p >= 0 && p < n_kv;
+  float m_max = -INFINITY;
+  for (int s = 0; s < n_parts; ++s)
+    m_max = fmaxf(m_max, sp.ml_part[(static_cast<int64_t>(s) * n_rows + row) * n_q_heads + head].x);
+  float l = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int s = 0; s < n_parts; ++s) {
+    const int64_t slot = (static_cast<int64_t>(s) * n_rows + row) * n_q_heads + head;
+    const float2 ml = sp.ml_part[slot];
+    if (ml.y > 0.f) {  // a part whose keys all lie behind this row's position holds (-inf, 0)
+      const float wgt = __builtin_amdgcn_exp2f(ml.x - m_max);
+      const float2 o = *reinterpret_cast<const float2 *>(sp.o_part + slot * D + 2 * lane);
+      l += ml.y * wgt;
+      o0 += o.x * wgt;
+      o1 += o.y * wgt;
+    }
+  }
+  const float inv = in_range && l > 0.f ? 1.f / l : 0.f;
+  const int64_t q = (static_cast<int64_t>(row) * n_q_heads + head);
+  *reinterpret_cast<uint32_t *>(out + q * D + 2 * lane) = pack_bf16x2(o0 * inv, o1 * inv);
+  if (lse_out != nullptr && lane == 0)
+    lse_out[q] = in_range && l > 0.f ? 0.6931471805599453f * (m_max + __log2f(l)) : 0.f;
+}
+
+// ---------------------------------------------------------------------------
 // NWAVES wavefronts, ring of NS LDS stages filled by direct global->LDS loads NS-1 tiles ahead.
 // ---------------------------------------------------------------------------
 template <int NWAVES, int NS>
@@ -397,7 +464,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ row_pos, int n_rows,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache, int n_kv,
     uint16_t *__restrict__ out, float *__restrict__ lse_out, int n_q_heads, int n_kv_heads, float scale_log2,
-    int rows_per_block) {
+    int rows_per_block, SplitPlan sp) {
   __shared__ __attribute__((aligned(1024))) uint16_t k_lds[NS][TILE_ELEMS];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds[NS][TILE_ELEMS];
   __shared__ int s_pmax[NWAVES];
@@ -407,11 +474,18 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   const int G = n_q_heads / n_kv_heads;
   const int g = blockIdx.x;
   const int rb = gridDim.y - 1 - blockIdx.y;  // longest prefixes are dispatched first
+  const int part = blockIdx.z;
   const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
                                 (threadIdx.x >> 6) * 32 + (lane & 31));
   bf16x8 qf[8];
   load_q_frags(qf, q_sel, c, hf);
   const int n_tiles = block_tiles<NWAVES>(c.p_wmax, s_pmax);
+  // this workgroup's share of the kv axis: tiles t0 .. t1-1 (the whole range unless the block is split)
+  const int t0 = part * sp.part_tiles;
+  const int t1 = min(n_tiles, t0 + sp.part_tiles);
+  if (t0 >= n_tiles) return;  // nothing left for this part (uniform over the workgroup)
+  const bool split = n_tiles > sp.part_tiles;
+  if (part == 0 && g == 0 && threadIdx.x == 0 && sp.block_tiles != nullptr) sp.block_tiles[rb] = n_tiles;
   const ReadOffsets ro = make_read_offsets(lane);
 
   const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
@@ -427,15 +501,15 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   w.m_run = -INFINITY;
   w.l_run = 0.f;
 
-  // Tiles 0 .. NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
+  // Tiles t0 .. t0+NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
   // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
-    issue_tile_dma<NWAVES>(plan, k_lds[t], v_lds[t], k_base, v_base, kv_row_elems, t, n_kv);
+    issue_tile_dma<NWAVES>(plan, k_lds[t], v_lds[t], k_base, v_base, kv_row_elems, t0 + t, n_kv);
 
-  const int my_tiles = min(n_tiles, c.p_wmax / TK + 1);
+  const int my_tiles = min(t1, c.p_wmax / TK + 1);
   int st = 0;  // ring position of tile i
-  for (int i = 0; i < n_tiles; ++i) {
+  for (int i = t0; i < t1; ++i) {
     // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
     // (loads complete in order; the query loads issued before them are therefore complete too)
     __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
@@ -457,7 +531,10 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     st = (st == NS - 1) ? 0 : st + 1;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is released
-  write_output(w, c, out, lse_out, n_q_heads, g, G, hf);
+  if (split)
+    write_partial(w, c, sp, part, n_rows, n_q_heads, g, G, hf);
+  else
+    write_output(w, c, out, lse_out, n_q_heads, g, G, hf);
 }
 
 
@@ -760,6 +837,57 @@ bool attention_mfma_supported(const ifkv_ctx *ctx) {
   return d.dtype == IFKV_BF16 && d.head_dim == D && G <= 32;
 }
 
+namespace {
+
+// How many parts the kv axis of the default kernel is cut into.  The chip holds 512 of these
+// workgroups at a time (two per CU).  When a launch has fewer jobs than about 1.5 per slot, the
+// longest row blocks alone set the finish time and cutting them pays (32K context, 5 % of the rows:
+// 0.66 -> 0.52 ms with two parts); with more jobs the greedy dispatch already evens them out and
+// the partial writes plus the combine pass cost more than the split gains (15 %: 1.28 -> 1.37 ms),
+// so those launches are not split.  A part spans at least 32 tiles.  IFKV_ATTN_SPLIT=<n> overrides
+// (tuning aid).
+struct SplitChoice {
+  int parts, part_tiles;
+};
+SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
+  const auto &d = ctx->desc;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const int rpb = 128 / G;
+  const int64_t jobs = ((n_rows + rpb - 1) / rpb) * d.n_kv_heads;
+  const int n_kv_tiles = static_cast<int>((n_kv + TK - 1) / TK);
+  int parts = 1;
+  if (const char *env = getenv("IFKV_ATTN_SPLIT")) {
+    parts = atoi(env);
+  } else if (jobs > 0 && jobs <= 768) {
+    parts = 2;
+    while (parts < 8 && jobs * parts < 768) parts *= 2;  // about two jobs per slot
+  }
+  const int max_parts = n_kv_tiles / 32 > 1 ? n_kv_tiles / 32 : 1;  // at least 32 tiles (2048 kv rows) per part
+  if (parts > max_parts) parts = max_parts;
+  if (parts > 8) parts = 8;
+  if (parts < 1) parts = 1;
+  SplitChoice c;
+  c.part_tiles = (n_kv_tiles + parts - 1) / parts;
+  if (c.part_tiles < 1) c.part_tiles = 1;
+  c.parts = (n_kv_tiles + c.part_tiles - 1) / c.part_tiles;
+  return c;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+}  // namespace
+
+size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
+  const auto &d = ctx->desc;
+  if ((d.flags & IFKV_FLAG_ATTN_WIDE) || n_rows <= 0) return 0;
+  const SplitChoice c = choose_split(ctx, n_rows, n_kv);
+  if (c.parts <= 1) return 0;
+  const size_t slots = static_cast<size_t>(c.parts) * static_cast<size_t>(n_rows) * d.n_q_heads;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const size_t n_rb = static_cast<size_t>((n_rows + 128 / G - 1) / (128 / G));
+  return align256(slots * D * sizeof(float)) + align256(slots * sizeof(float2)) + align256(n_rb * sizeof(int));
+}
+
 hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                                  const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                                  float *lse_out) {
@@ -778,23 +906,31 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
       return hipGetLastError();
     }
   }
-  // IFKV_ATTN_WAVES=8 selects the 256-column variant (tuning aid).
-  const int rpb8 = 256 / G;
-  bool big = false;
-  if (const char *env = getenv("IFKV_ATTN_WAVES")) big = atoi(env) == 8;
-  const int rpb = big ? rpb8 : 128 / G;
+  const int rpb = 128 / G;
   const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
-  dim3 grid(d.n_kv_heads, n_rb);
-  if (big) {
-    hipLaunchKernelGGL((attn_mfma_kernel<8, 3>), grid, dim3(512), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
-                       row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
-                       static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
-                       lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb);
-  } else {
-    hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
-                       row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
-                       static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
-                       lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb);
+  const SplitChoice sc = choose_split(ctx, n_rows, n_kv);
+  SplitPlan sp;
+  sp.part_tiles = sc.part_tiles;
+  sp.o_part = nullptr;
+  sp.ml_part = nullptr;
+  sp.block_tiles = nullptr;
+  if (sc.parts > 1) {
+    const size_t slots = static_cast<size_t>(sc.parts) * static_cast<size_t>(n_rows) * d.n_q_heads;
+    char *base = static_cast<char *>(ctx->scratch);
+    sp.o_part = reinterpret_cast<float *>(base);
+    sp.ml_part = reinterpret_cast<float2 *>(base + align256(slots * D * sizeof(float)));
+    sp.block_tiles = reinterpret_cast<int *>(base + align256(slots * D * sizeof(float)) + align256(slots * sizeof(float2)));
+  }
+  dim3 grid(d.n_kv_heads, n_rb, sc.parts);
+  hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
+                     row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
+                     static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
+                     lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb, sp);
+  if (sc.parts > 1) {
+    const int64_t items = n_rows * d.n_q_heads;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, ctx->stream, sp,
+                       row_pos, static_cast<int>(n_rows), static_cast<int>(n_kv), d.n_q_heads, rpb,
+                       static_cast<uint16_t *>(out), lse_out);
   }
   return hipGetLastError();
 }

@@ -351,6 +351,18 @@ def attention_case_subsampled(spec, rows, n_check, flags=0):
     return to_host_f64(out, spec.dtype)[pick], lse.cpu().numpy().astype(np.float64)[pick], ref, lse_ref
 
 
+@pytest.mark.parametrize("parts", ["2", "3"])
+def test_attention_split_over_kv_axis(parts, monkeypatch):
+    """The default kernel with its kv axis cut into parts (partial results in scratch + combine pass),
+    forced here; by itself the library splits only launches with few row blocks."""
+    monkeypatch.setenv("IFKV_ATTN_SPLIT", parts)
+    spec = preset("C2", chunk_lens=[640] * 10, m_prompt=8)            # 100 kv tiles
+    rows = np.unique(np.concatenate([sample_rows(6400, 900, 5), [0, 63, 64, 2111, 2112, 2113, 4223, 4224, 6399]]))
+    out, lse, ref, lse_ref = attention_case_subsampled(spec, rows, 200)
+    assert np.abs(out - ref).max() <= 2e-2, np.abs(out - ref).max()
+    assert np.abs(lse - lse_ref).max() <= 2e-2
+
+
 @pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
 def test_attention_full_ratio_is_dense_causal(flags):
     spec = preset("C2", chunk_lens=[150, 83], m_prompt=8)
