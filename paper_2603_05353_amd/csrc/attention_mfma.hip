@@ -237,18 +237,15 @@ __device__ __forceinline__ void pv_tile(const PTile &P, VFrags &f, WaveState &w,
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
   return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void *)p));
 }
-// per-lane 64-bit global address
-__device__ __forceinline__ void dma16(const void *global_src, const void *lds_dst) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-               :
-               : "v"(global_src), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds_dst)))
-               : "memory");
+// per-lane 64-bit global address; lds_dst: wavefront-uniform LDS byte address of the instruction
+__device__ __forceinline__ void dma16(const void *global_src, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(global_src), "s"(lds_dst) : "memory");
 }
 // wavefront-uniform 64-bit base + per-lane 32-bit byte offset
-__device__ __forceinline__ void dma16_base(const void *uniform_base, uint32_t lane_offset, const void *lds_dst) {
+__device__ __forceinline__ void dma16_base(const void *uniform_base, uint32_t lane_offset, uint32_t lds_dst) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                :
-               : "v"(lane_offset), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds_dst)))
+               : "v"(lane_offset), "s"(uniform_base), "s"(lds_dst)
                : "memory");
 }
 
@@ -282,11 +279,13 @@ __device__ __forceinline__ DmaPlan<NWAVES> make_dma_plan(int64_t kv_row_elems) {
   return pl;
 }
 
+// k_stage / v_stage: wavefront-uniform LDS byte addresses of the stage to fill (plain integers, so
+// the per-instruction LDS base is scalar arithmetic and costs no vector instruction)
 template <int NWAVES>
-__device__ __forceinline__ void issue_tile_dma(const DmaPlan<NWAVES> &pl, uint16_t *k_stage, uint16_t *v_stage,
+__device__ __forceinline__ void issue_tile_dma(const DmaPlan<NWAVES> &pl, uint32_t k_stage, uint32_t v_stage,
                                                const uint16_t *k_base, const uint16_t *v_base, int64_t kv_row_elems,
                                                int tile, int n_kv) {
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t unit0 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * Dma<NWAVES>::UPW;
   int j0 = tile * TK;
   const bool partial = (j0 < n_kv && j0 + TK > n_kv) || n_kv < TK;
   if (!partial) {
@@ -295,9 +294,8 @@ __device__ __forceinline__ void issue_tile_dma(const DmaPlan<NWAVES> &pl, uint16
     const uint16_t *vb = v_base + j0 * kv_row_elems;
 #pragma unroll
     for (int x = 0; x < Dma<NWAVES>::UPW; ++x) {
-      const int unit = wave * Dma<NWAVES>::UPW + x;
-      dma16_base(kb, pl.k_off[x], k_stage + unit * 512);
-      dma16_base(vb, pl.v_off[x], v_stage + unit * 512);
+      dma16_base(kb, pl.k_off[x], k_stage + (unit0 + x) * 1024u);
+      dma16_base(vb, pl.v_off[x], v_stage + (unit0 + x) * 1024u);
     }
   } else {
     // the one tile that straddles the end of the cache: rows past the end are clamped (and masked later)
@@ -305,12 +303,12 @@ __device__ __forceinline__ void issue_tile_dma(const DmaPlan<NWAVES> &pl, uint16
     const int r = lane >> 4, cpos = lane & 15;
 #pragma unroll
     for (int x = 0; x < Dma<NWAVES>::UPW; ++x) {
-      const int unit = wave * Dma<NWAVES>::UPW + x;
+      const uint32_t unit = unit0 + x;
       const int i = 4 * unit + r;
       const int jk = min(j0 + sigma(i), n_kv - 1);
       const int jv = min(j0 + i, n_kv - 1);
-      dma16(k_base + jk * kv_row_elems + 8 * (cpos ^ (i & 15)), k_stage + unit * 512);
-      dma16(v_base + jv * kv_row_elems + 8 * (cpos ^ (4 * r)), v_stage + unit * 512);
+      dma16(k_base + jk * kv_row_elems + 8 * (cpos ^ (i & 15)), k_stage + unit * 1024u);
+      dma16(v_base + jv * kv_row_elems + 8 * (cpos ^ (4 * r)), v_stage + unit * 1024u);
     }
   }
 }
@@ -493,6 +491,10 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
   const auto plan = make_dma_plan<NWAVES>(kv_row_elems);
 
+  const uint32_t k_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&k_lds[0][0]));
+  const uint32_t v_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&v_lds[0][0]));
+  constexpr uint32_t kStageBytes = TILE_ELEMS * 2;
+
   WaveState w;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -505,30 +507,45 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
-    issue_tile_dma<NWAVES>(plan, k_lds[t], v_lds[t], k_base, v_base, kv_row_elems, t0 + t, n_kv);
+    issue_tile_dma<NWAVES>(plan, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
+                           kv_row_elems, t0 + t, n_kv);
 
   const int my_tiles = min(t1, c.p_wmax / TK + 1);
-  int st = 0;  // ring position of tile i
-  for (int i = t0; i < t1; ++i) {
+  // One tile.  `st` is a compile-time constant at every call (the loop below is unrolled over the
+  // ring), so the LDS stage base folds into the immediate offset of every LDS read and the reads
+  // cost no address arithmetic.
+  auto tile_step = [&](int i, int st) {
     // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
     // (loads complete in order; the query loads issued before them are therefore complete too)
     __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
     __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
     {
       const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
-      issue_tile_dma<NWAVES>(plan, k_lds[wr], v_lds[wr], k_base, v_base, kv_row_elems, i + NS - 1, n_kv);
+      issue_tile_dma<NWAVES>(plan, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
+                             kv_row_elems, i + NS - 1, n_kv);
     }
     if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
       f32x16 S[2];
+      // The matrix phases run at a raised priority: when the other wavefront of the SIMD is in its
+      // softmax, this one's MFMAs are issued the moment the pipe is free and the vector work fills
+      // the gaps (3 % on all-zero inputs, 1 % under the power cap).
+      __builtin_amdgcn_s_setprio(1);
       qk_tile(S, k_lds[st], qf, ro);
       VFrags vf;
       pv_preload(vf, v_lds[st], ro);
+      __builtin_amdgcn_s_setprio(0);
       row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
       PTile P;
       exp_tile(S, w, P, scale_log2);
+      __builtin_amdgcn_s_setprio(1);
       pv_tile(P, vf, w, v_lds[st], ro);
+      __builtin_amdgcn_s_setprio(0);
     }
-    st = (st == NS - 1) ? 0 : st + 1;
+  };
+  for (int i0 = t0; i0 < t1; i0 += NS) {
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+      if (i0 + st < t1) tile_step(i0 + st, st);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is released
   if (split)
@@ -787,11 +804,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   wA.l_run = wB.l_run = 0.f;
 
   // Prologue: tiles 0 and 1 staged; S and softmax of half tile 0 and S of half tile 1 without overlap.
-  issue_tile_dma<NW>(plan, k_lds[0], v_lds[0], k_base, v_base, kv_row_elems, 0, n_kv);
-  issue_tile_dma<NW>(plan, k_lds[1], v_lds[1], k_base, v_base, kv_row_elems, 1, n_kv);
+  const uint32_t k_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&k_lds[0][0]));
+  const uint32_t v_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&v_lds[0][0]));
+  constexpr uint32_t kStageBytes = TILE_ELEMS * 2;
+  issue_tile_dma<NW>(plan, k_lds_addr, v_lds_addr, k_base, v_base, kv_row_elems, 0, n_kv);
+  issue_tile_dma<NW>(plan, k_lds_addr + kStageBytes, v_lds_addr + kStageBytes, k_base, v_base, kv_row_elems, 1, n_kv);
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
-  issue_tile_dma<NW>(plan, k_lds[2], v_lds[2], k_base, v_base, kv_row_elems, 2, n_kv);
+  issue_tile_dma<NW>(plan, k_lds_addr + 2 * kStageBytes, v_lds_addr + 2 * kStageBytes, k_base, v_base, kv_row_elems, 2,
+                     n_kv);
 
   // S0/P0 belong to the first half of a tile, S1/P1 to the second.
   f32x16 S0A, S0B, S1A, S1B;
@@ -814,7 +835,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // free once every wavefront has passed the barrier
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    issue_tile_dma<NW>(plan, k_lds[(i + 2) & 3], v_lds[(i + 2) & 3], k_base, v_base, kv_row_elems, i + 2, n_kv);
+    issue_tile_dma<NW>(plan, k_lds_addr + ((i + 2) & 3) * kStageBytes, v_lds_addr + ((i + 2) & 3) * kStageBytes, k_base,
+                       v_base, kv_row_elems, i + 2, n_kv);
     // first half of tile i: adds the second half of tile i-1, multiplies the second half of tile i
     wide_step(wA, wB, qA, qB, P1A, P1B, P0A, P0B, S0A, S0B, S1A, S1B, v_lds[(i - 1) & 3], 1, k_lds[i & 3], 1, ro, ln,
               i * TK);
