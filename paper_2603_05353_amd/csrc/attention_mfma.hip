@@ -526,20 +526,13 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     }
     if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
       f32x16 S[2];
-      // The matrix phases run at a raised priority: when the other wavefront of the SIMD is in its
-      // softmax, this one's MFMAs are issued the moment the pipe is free and the vector work fills
-      // the gaps (3 % on all-zero inputs, 1 % under the power cap).
-      __builtin_amdgcn_s_setprio(1);
       qk_tile(S, k_lds[st], qf, ro);
       VFrags vf;
       pv_preload(vf, v_lds[st], ro);
-      __builtin_amdgcn_s_setprio(0);
       row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
       PTile P;
       exp_tile(S, w, P, scale_log2);
-      __builtin_amdgcn_s_setprio(1);
       pv_tile(P, vf, w, v_lds[st], ro);
-      __builtin_amdgcn_s_setprio(0);
     }
   };
   for (int i0 = t0; i0 < t1; i0 += NS) {
