@@ -249,6 +249,8 @@ int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double r
   if (k_out != nullptr) *k_out = k;
   if (k == 0) return IFKV_OK;
   if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk: NULL pointer");
+  int rc = ensure_scratch(ctx, ifkv::topk_scratch_bytes(ctx, n_ctx));
+  if (rc != IFKV_OK) return rc;
   hipError_t e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "top-k kernel launch");
 }

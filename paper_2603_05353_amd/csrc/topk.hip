@@ -12,6 +12,9 @@
 //
 // Ties are resolved towards the smaller index and the result is emitted in
 // ascending index order by a block-wide prefix sum over (greater, tie) counts.
+//
+// Vectors of more than 32768 scores do not fit one workgroup's registers; they take the
+// multi-workgroup radix select further down (six short launches).
 #include "ifkv_device.h"
 #include "ifkv_internal.h"
 
@@ -238,90 +241,211 @@ __global__ __launch_bounds__(THREADS) void topk_resident_kernel(const float *__r
 }
 
 // ---------------------------------------------------------------------------
-// Fallback for score vectors beyond the register-resident capacity: the same
-// selection by bitwise descent, re-reading the scores from L2/HBM at every
-// step.  Correct for any n < 2^31, linear in n per step.
+// Score vectors beyond the register-resident capacity: radix select over many workgroups.
+// The key's 32 bits are resolved in three digits (11 + 11 + 10 bits).  Pass p counts, per digit
+// value, the keys that match the prefix found so far (LDS histogram per workgroup, then one global
+// atomic add per non-empty bin: integer counts, so the result does not depend on the order); the
+// next kernel starts by locating the digit that holds the k-th largest key in that histogram (every
+// workgroup redoes this small scan, which saves a launch per pass).  After the third digit the
+// threshold key T is exact; the last two kernels count (greater, tie) elements per workgroup and
+// write the indices in ascending order, taking ties by ascending index.
+// Near-uniform attention puts most keys into one bin of the first digit; the cost is LDS atomics on
+// one address (a few hundred cycles per workgroup), not correctness.
 // ---------------------------------------------------------------------------
-constexpr int kStreamThreads = 1024;
+constexpr int kSelThreads = 256;
+constexpr int kSelPer = 16;                       // keys per thread
+constexpr int kSelChunk = kSelThreads * kSelPer;  // keys per workgroup
+constexpr int kSelBins = 2048;
 
-template <bool STRICT>
-__device__ __forceinline__ int block_count_above(const float *__restrict__ scores, int n, uint32_t cand,
-                                                 uint32_t *red, int slot) {
-  int c = 0;
-  for (int i = threadIdx.x; i < n; i += kStreamThreads) {
-    const uint32_t key = score_key(scores[i]);
-    c += STRICT ? (key > cand) : (key >= cand);
-  }
-  c = wave64_sum(c);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  if (lane == 0) red[slot * 16 + wave] = static_cast<uint32_t>(c);
+struct SelectState {  // lives in scratch
+  uint32_t hist[3][kSelBins];
+};
+__device__ __forceinline__ int digit_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ uint32_t digit_mask(int pass) { return pass == 2 ? 0x3FFu : 0x7FFu; }
+
+// Locates, in the histogram of pass `pass`, the digit that holds the need-th largest key among
+// the keys matching `prefix`; returns it and lowers `need` by the keys in higher digits.
+// Called by every thread of a 256-thread workgroup with the same arguments; `red` holds 257 ints.
+__device__ __forceinline__ uint32_t locate_digit(const uint32_t *__restrict__ hist, int pass, int &need, int *red) {
+  const int nb = pass == 2 ? 1024 : kSelBins;
+  const int per = nb / kSelThreads;  // consecutive bins per thread (8 or 4)
+  const int tid = threadIdx.x;
+  // thread t owns bins [nb - (t+1)*per, nb - t*per): thread 0 the highest digits
+  int mine = 0;
+  for (int e = 0; e < per; ++e) mine += static_cast<int>(hist[nb - 1 - (tid * per + e)]);
+  red[tid] = mine;
   __syncthreads();
-  int t = (lane < kStreamThreads / 64) ? static_cast<int>(red[slot * 16 + lane]) : 0;
-  return __builtin_amdgcn_readlane(row16_sum(t), 0);
+  if (tid == 0) {  // 256-entry exclusive scan: short, and only here
+    int acc = 0;
+    for (int t = 0; t < kSelThreads; ++t) {
+      const int v = red[t];
+      red[t] = acc;
+      acc += v;
+    }
+    red[kSelThreads] = acc;
+  }
+  __syncthreads();
+  const int before = red[tid];  // keys in digits above this thread's bins
+  __syncthreads();
+  if (before < need && need <= before + mine) {  // exactly one thread
+    int acc = before;
+    for (int e = 0; e < per; ++e) {
+      const int bin = nb - 1 - (tid * per + e);
+      const int c = static_cast<int>(hist[bin]);
+      if (need <= acc + c) {
+        red[0] = bin;
+        red[1] = need - acc;
+        break;
+      }
+      acc += c;
+    }
+  }
+  __syncthreads();
+  const uint32_t digit = static_cast<uint32_t>(red[0]);
+  need = red[1];
+  __syncthreads();
+  return digit;
 }
 
-__global__ __launch_bounds__(kStreamThreads) void topk_streaming_kernel(const float *__restrict__ scores, int n,
-                                                                        int k, int32_t *__restrict__ idx_out) {
-  __shared__ uint32_t red[2 * 16];
-  __shared__ uint32_t wave_tot[16];
+// Replays the digits found so far: prefix of the threshold key and the remaining rank.
+__device__ __forceinline__ uint32_t replay_prefix(const SelectState *st, int passes_done, int k, int &need, int *red) {
+  uint32_t prefix = 0;
+  need = k;
+  for (int p = 0; p < passes_done; ++p) prefix |= locate_digit(st->hist[p], p, need, red) << digit_shift(p);
+  return prefix;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_hist_kernel(const float *__restrict__ scores, int n, int k,
+                                                                  int pass, SelectState *__restrict__ st) {
+  __shared__ uint32_t lh[kSelBins];
+  __shared__ int red[kSelThreads + 1];
+  for (int b = threadIdx.x; b < kSelBins; b += kSelThreads) lh[b] = 0u;
+  __syncthreads();
+  int need;
+  const uint32_t prefix = replay_prefix(st, pass, k, need, red);
+  const uint32_t hi_mask = pass == 0 ? 0u : (pass == 1 ? 0xFFE00000u : 0xFFFFFC00u);
+  const int sh = digit_shift(pass);
+  const uint32_t dm = digit_mask(pass);
+  const int base = blockIdx.x * kSelChunk;
+#pragma unroll 4
+  for (int e = 0; e < kSelPer; ++e) {
+    const int i = base + e * kSelThreads + threadIdx.x;
+    if (i < n) {
+      const uint32_t key = score_key(scores[i]);
+      if ((key & hi_mask) == prefix) atomicAdd(&lh[(key >> sh) & dm], 1u);
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < kSelBins; b += kSelThreads)
+    if (lh[b] != 0u) atomicAdd(&st->hist[pass][b], lh[b]);
+}
+
+// Per workgroup: how many keys are above the threshold and how many equal it.
+__global__ __launch_bounds__(kSelThreads) void select_count_kernel(const float *__restrict__ scores, int n, int k,
+                                                                   const SelectState *__restrict__ st,
+                                                                   uint2 *__restrict__ block_counts) {
+  __shared__ int red[kSelThreads + 1];
+  __shared__ uint32_t wsum[2][kSelThreads / 64];
+  int need;
+  const uint32_t T = replay_prefix(st, 3, k, need, red);
+  const int base = blockIdx.x * kSelChunk + threadIdx.x * kSelPer;
+  int g = 0, t = 0;
+#pragma unroll 4
+  for (int e = 0; e < kSelPer; ++e)
+    if (base + e < n) {
+      const uint32_t key = score_key(scores[base + e]);
+      g += key > T;
+      t += key == T;
+    }
+  g = wave64_sum(g);
+  t = wave64_sum(t);
+  if ((threadIdx.x & 63) == 0) {
+    wsum[0][threadIdx.x >> 6] = g;
+    wsum[1][threadIdx.x >> 6] = t;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t gs = 0, ts = 0;
+    for (int w = 0; w < kSelThreads / 64; ++w) {
+      gs += wsum[0][w];
+      ts += wsum[1][w];
+    }
+    block_counts[blockIdx.x] = make_uint2(gs, ts);
+  }
+}
+
+// Ordered output.  Thread t of workgroup b owns keys [b*chunk + t*16, +16): a contiguous run, so
+// ascending index order is (workgroup, thread, element).
+__global__ __launch_bounds__(kSelThreads) void select_write_kernel(const float *__restrict__ scores, int n, int k,
+                                                                   const SelectState *__restrict__ st,
+                                                                   const uint2 *__restrict__ block_counts,
+                                                                   int32_t *__restrict__ idx_out) {
+  __shared__ int red[kSelThreads + 1];
+  __shared__ uint32_t wave_tot[kSelThreads / 64];
+  int need;
+  const uint32_t T = replay_prefix(st, 3, k, need, red);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-  uint32_t T = 0;
-  for (int b = 31; b >= 0; --b) {
-    const uint32_t cand = T | (1u << b);
-    const int cnt = block_count_above<false>(scores, n, cand, red, b & 1);
-    if (cnt >= k) T = cand;
+  // elements taken by the workgroups before this one
+  uint32_t g_before = 0, t_before = 0;
+  for (int b = tid; b < static_cast<int>(blockIdx.x); b += kSelThreads) {
+    const uint2 c = block_counts[b];
+    g_before += c.x;
+    t_before += c.y;
   }
-  const int n_greater = block_count_above<true>(scores, n, T, red, 1);  // slot 0 may still be read
-  const int need = k - n_greater;
-
-  constexpr int PER = 8;
-  int carry_g = 0, carry_t = 0;
-  for (int base = 0; base < n; base += kStreamThreads * PER) {
-    const int i0 = base + tid * PER;
-    uint32_t gm = 0, tm = 0;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      if (i0 + e < n) {
-        const uint32_t key = score_key(scores[i0 + e]);
-        gm |= (key > T ? 1u : 0u) << e;
-        tm |= (key == T ? 1u : 0u) << e;
-      }
-    }
-    const uint32_t v = static_cast<uint32_t>(__popc(gm)) | (static_cast<uint32_t>(__popc(tm)) << 16);
-    uint32_t incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t up = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += up;
-    }
-    __syncthreads();
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t wave_before = 0, block_total = 0;
-#pragma unroll
-    for (int x = 0; x < kStreamThreads / 64; ++x) {
-      const uint32_t wt = wave_tot[x];
-      if (x < wave) wave_before += wt;
-      block_total += wt;
-    }
-    const uint32_t excl = wave_before + incl - v;
-    int t_seen = carry_t + static_cast<int>(excl >> 16);
-    int pos = carry_g + static_cast<int>(excl & 0xFFFFu) + min(t_seen, need);
-    uint32_t m = gm | tm;
-    while (m) {
-      const int i = __ffs(m) - 1;
-      m &= m - 1;
-      bool take = (gm >> i) & 1u;
-      if (!take) take = (t_seen++ < need);
-      if (take) {
-        if (pos < k) idx_out[pos] = i0 + i;
-        ++pos;
-      }
-    }
-    carry_g += static_cast<int>(block_total & 0xFFFFu);
-    carry_t += static_cast<int>(block_total >> 16);
+  g_before = static_cast<uint32_t>(wave64_sum(static_cast<int>(g_before)));
+  t_before = static_cast<uint32_t>(wave64_sum(static_cast<int>(t_before)));
+  __shared__ uint32_t pre[2][kSelThreads / 64];
+  if (lane == 0) {
+    pre[0][wave] = g_before;
+    pre[1][wave] = t_before;
   }
+  __syncthreads();
+  g_before = 0;
+  t_before = 0;
+  for (int w = 0; w < kSelThreads / 64; ++w) {
+    g_before += pre[0][w];
+    t_before += pre[1][w];
+  }
+  const int base = blockIdx.x * kSelChunk + tid * kSelPer;
+  uint32_t gm = 0, tm = 0;
+#pragma unroll 4
+  for (int e = 0; e < kSelPer; ++e)
+    if (base + e < n) {
+      const uint32_t key = score_key(scores[base + e]);
+      gm |= (key > T ? 1u : 0u) << e;
+      tm |= (key == T ? 1u : 0u) << e;
+    }
+  // (greater, tie) counts packed in one word: a workgroup holds 4096 keys, so 16 bits each suffice
+  const uint32_t v = static_cast<uint32_t>(__popc(gm)) | (static_cast<uint32_t>(__popc(tm)) << 16);
+  uint32_t incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t wave_before = 0;
+  for (int x = 0; x < wave; ++x) wave_before += wave_tot[x];
+  const uint32_t excl = wave_before + incl - v;
+  int t_seen = static_cast<int>(t_before + (excl >> 16));
+  int pos = static_cast<int>(g_before + (excl & 0xFFFFu)) + min(t_seen, need);
+  uint32_t m = gm | tm;
+  while (m) {
+    const int i = __ffs(m) - 1;
+    m &= m - 1;
+    bool take = (gm >> i) & 1u;
+    if (!take) take = (t_seen++ < need);
+    if (take) {
+      if (pos < k) idx_out[pos] = base + i;  // pos < k always holds; the guard keeps a logic slip in bounds
+      ++pos;
+    }
+  }
+}
+
+__global__ void select_zero_kernel(SelectState *st) {
+  uint32_t *p = &st->hist[0][0];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < 3 * kSelBins; i += gridDim.x * blockDim.x) p[i] = 0u;
 }
 
 // "Chunk Reordering", Eq. (9), numerator: idx is ascending, so the rows of slot s are the
@@ -355,7 +479,11 @@ hipError_t launch_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, con
   return hipGetLastError();
 }
 
-size_t topk_scratch_bytes(const ifkv_ctx *, int64_t) { return 0; }
+size_t topk_scratch_bytes(const ifkv_ctx *, int64_t n_ctx) {
+  if (n_ctx <= 1024 * 32) return 0;
+  const size_t blocks = static_cast<size_t>((n_ctx + kSelChunk - 1) / kSelChunk);
+  return ((sizeof(SelectState) + 255) & ~static_cast<size_t>(255)) + blocks * sizeof(uint2);
+}
 
 hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out) {
   if (k <= 0 || n_ctx <= 0) return hipSuccess;
@@ -367,7 +495,16 @@ hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_
   } else if (n <= 1024 * 32) {
     hipLaunchKernelGGL((topk_resident_kernel<1024, 1>), dim3(1), dim3(1024), 0, st, scores, n, kk, idx_out);
   } else {
-    hipLaunchKernelGGL(topk_streaming_kernel, dim3(1), dim3(kStreamThreads), 0, st, scores, n, kk, idx_out);
+    SelectState *state = static_cast<SelectState *>(ctx->scratch);
+    uint2 *counts = reinterpret_cast<uint2 *>(static_cast<char *>(ctx->scratch) +
+                                              ((sizeof(SelectState) + 255) & ~static_cast<size_t>(255)));
+    const unsigned blocks = static_cast<unsigned>((n + kSelChunk - 1) / kSelChunk);
+    hipLaunchKernelGGL(select_zero_kernel, dim3(6), dim3(1024), 0, st, state);
+    for (int pass = 0; pass < 3; ++pass)
+      hipLaunchKernelGGL(select_hist_kernel, dim3(blocks), dim3(kSelThreads), 0, st, scores, n, kk, pass, state);
+    hipLaunchKernelGGL(select_count_kernel, dim3(blocks), dim3(kSelThreads), 0, st, scores, n, kk, state, counts);
+    hipLaunchKernelGGL(select_write_kernel, dim3(blocks), dim3(kSelThreads), 0, st, scores, n, kk, state, counts,
+                       idx_out);
   }
   return hipGetLastError();
 }
