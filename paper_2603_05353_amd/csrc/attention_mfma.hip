@@ -855,11 +855,12 @@ bool attention_mfma_supported(const ifkv_ctx *ctx) {
 namespace {
 
 // How many parts the kv axis of the default kernel is cut into.  The chip holds 512 of these
-// workgroups at a time (two per CU).  When a launch has fewer jobs than about 1.5 per slot, the
-// longest row blocks alone set the finish time and cutting them pays (32K context, 5 % of the rows:
-// 0.66 -> 0.52 ms with two parts); with more jobs the greedy dispatch already evens them out and
-// the partial writes plus the combine pass cost more than the split gains (15 %: 1.28 -> 1.37 ms),
-// so those launches are not split.  A part spans at least 32 tiles.  IFKV_ATTN_SPLIT=<n> overrides
+// workgroups at a time (two per CU).  When a launch has no more jobs than slots, the longest row
+// blocks alone set the finish time and cutting them pays (32K context, 5 % of the rows, 416 jobs:
+// 0.66 -> 0.52 ms with two parts; 8K context, 312 jobs: 0.150 -> 0.130 ms); with more jobs the
+// greedy dispatch already evens them out and the partial writes plus the combine pass cost more
+// than the split gains (684 jobs: 0.465 -> 0.496 ms; 1232 jobs: 1.28 -> 1.37 ms), so those
+// launches are not split.  A part spans at least 32 tiles.  IFKV_ATTN_SPLIT=<n> overrides
 // (tuning aid).
 struct SplitChoice {
   int parts, part_tiles;
@@ -873,7 +874,7 @@ SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
   int parts = 1;
   if (const char *env = getenv("IFKV_ATTN_SPLIT")) {
     parts = atoi(env);
-  } else if (jobs > 0 && jobs <= 768) {
+  } else if (jobs > 0 && jobs <= 512) {
     parts = 2;
     while (parts < 8 && jobs * parts < 768) parts *= 2;  // about two jobs per slot
   }
