@@ -484,6 +484,42 @@ def test_composite_layer(cfg, rtol_sel):
 
 
 # ---------------------------------------------------------------------------
+# the other RoPE geometries of the appendix ("RoPE Geometry"), expressed through delta_override
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("geometry", ["HL-TP", "HL-HP", "TL-TP"])
+def test_scores_under_other_rope_geometries(geometry):
+    """Head-local context (every chunk keeps positions 0..len-1), tail-local context (every chunk ends
+    right before the prompt: advance N - len_i) and the two prompt placements (tail = global position N,
+    head = right after the longest chunk).  Reading: "immediately before/after" is taken per chunk.
+    The library only sees phase advances and already-rotated prompt queries; the scores and the selected
+    set must match the oracle run with the same advances."""
+    from workloads import rope_at
+    spec = preset("C2", chunk_lens=[180, 75, 260, 141], m_prompt=16, permute_order=True)
+    wl = make_workload(spec)
+    k, _, q = oracle_inputs(wl)
+    N, lens, order = wl.n_ctx, [int(x) for x in wl.chunk_len], wl.chunk_order.tolist()
+    adv = [N - L_i for L_i in lens] if geometry == "TL-TP" else [0] * len(lens)
+    if geometry == "HL-HP":   # prompt moved from N.. to max(len).. : queries rotate by the difference
+        q = rope_at(q, float(max(lens) - N), spec.rope_theta, spec.pairing)
+    q_st = to_storage(q, spec.dtype)
+    q = to_f64(q_st, spec.dtype)
+    L = make_layer(spec, max_ctx=N, max_prompt=spec.m_prompt)
+    kd, _ = dev_chunks(wl)
+    K, _, _, _ = L.reposition_keys(kd, None, chunk_order=order, delta_override=adv)
+    s = L.score_tokens(K, to_dev(q_st, spec.dtype))
+    idx = L.select_topk(s, ratio=0.15)
+    sync()
+    K_ref, _, _, _ = O.reposition_keys(k, None, lens, order, spec.rope_theta, spec.pairing, delta_override=adv)
+    check_reposition(to_host_f64(K, spec.dtype), K_ref, spec.dtype, spec.pairing)
+    # score the stored keys the GPU produced, so both sides see identical inputs
+    s_ref = O.score_tokens(to_host_f64(K, spec.dtype), q, wl.sm_scale)
+    s_h = s.cpu().numpy()
+    assert (np.abs(s_h - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all()
+    assert np.array_equal(idx.cpu().numpy().astype(np.int64), O.select_topk(s_h, O.budget(N, 0.15)))
+    L.close()
+
+
+# ---------------------------------------------------------------------------
 # chunk reordering
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("n_slots,n_ctx,k", [(1, 100, 30), (4, 1024, 153), (64, 32768, 4915), (100, 5000, 700),
