@@ -761,15 +761,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const Column cA = setup_column(row_pos, n_rows, n_kv, row0, rows_per_block, G, g, n_q_heads, wave * 64 + (lane & 31));
   const Column cB =
       setup_column(row_pos, n_rows, n_kv, row0, rows_per_block, G, g, n_q_heads, wave * 64 + 32 + (lane & 31));
-  // Query fragments go from memory straight into the accumulation half of the register file; the
-  // compiler does not know these loads are pending: the vmcnt(0) wait before the first barrier below
-  // covers them.  Columns without a row read a clamped (valid) row and are never written back.
+  // Query fragments go from memory straight into the accumulation half of the register file.  The
+  // compiler does not know that these statements are loads, so the wait for them is part of the same
+  // dependency chain: the statement after the loop waits for all outstanding loads and names every
+  // fragment as read and written, which keeps any later use (or register copy) behind the wait.
+  // Columns without a row read a clamped (valid) row and are never written back.
   v4u qA[8], qB[8];
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(qA[x]) : "v"(q_sel + cA.q_off + 16 * x + 8 * hf) : "memory");
     asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(qB[x]) : "v"(q_sel + cB.q_off + 16 * x + 8 * hf) : "memory");
   }
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+a"(qA[0]), "+a"(qA[1]), "+a"(qA[2]), "+a"(qA[3]), "+a"(qA[4]), "+a"(qA[5]), "+a"(qA[6]), "+a"(qA[7]),
+                 "+a"(qB[0]), "+a"(qB[1]), "+a"(qB[2]), "+a"(qB[3]), "+a"(qB[4]), "+a"(qB[5]), "+a"(qB[6]), "+a"(qB[7])
+               :
+               : "memory");
   const int n_tiles = block_tiles<NW>(max(cA.p_wmax, cB.p_wmax), s_pmax);
   const ReadOffsets ro = make_read_offsets(lane);
   WideLane ln;
