@@ -488,3 +488,23 @@ def test_reorder_pass_is_local_geometry_then_density_sort():
     assert counts.tolist() == want_counts
     want_order = sorted(order, key=lambda c: Fraction(want_counts[c], int(wl.chunk_len[c])))
     assert new_order.tolist() == want_order
+
+
+# --------------------------------------------------------------------------
+# rotary embedding of recomputed rows
+# --------------------------------------------------------------------------
+def test_rope_rows_against_complex_multiplication_and_composition():
+    g = rng(51)
+    for pairing in ("half", "interleaved"):
+        x = g.standard_normal((7, 3, 8))
+        pos = np.array([0, 1, 5, 17, 1000, 40000, 131071])
+        got = O.rope_rows(x, pos, 10000.0, pairing)
+        assert np.allclose(got, rope_scratch_complex(x, pos, 10000.0, pairing), rtol=0, atol=1e-9)
+        assert np.array_equal(got[0], x[0])                       # position 0: identity
+        # rotations add: rotating rows placed at p by a further q equals placing them at p + q
+        again = O.rope_rows(got, np.full(7, 23), 10000.0, pairing)
+        assert np.allclose(again, O.rope_rows(x, pos + 23, 10000.0, pairing), rtol=0, atol=1e-9)
+        # per-pair norms are preserved
+        n0 = np.hypot(x[..., :4], x[..., 4:]) if pairing == "half" else np.hypot(x[..., 0::2], x[..., 1::2])
+        n1 = np.hypot(got[..., :4], got[..., 4:]) if pairing == "half" else np.hypot(got[..., 0::2], got[..., 1::2])
+        assert np.allclose(n0, n1, rtol=1e-12)
