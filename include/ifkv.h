@@ -241,6 +241,24 @@ int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new,
                    void *k_cache, void *v_cache, int64_t n_kv);
 
 /*
+ * Glue between the model's projections and stages 4/5 -- "KV Recomputation":
+ * a selected token runs a standard forward pass "placed at its global
+ * position", so its freshly projected query and key rows carry the rotary
+ * embedding of Eq. (3)-(4) at that position.  Row r of x is turned, in every
+ * 2-D pair j, by pos[r] * theta_j; angles are formed in fp64, the rotation runs
+ * in fp32 and is rounded once to the storage dtype.  In place.  (The
+ * projections themselves need the model's weights and are not part of this
+ * library.)
+ *
+ *   x        device [n_rows, n_heads, d], 16-byte aligned, updated in place
+ *   pos      device int32 [n_rows], the rows' global positions (e.g. the index
+ *            list of ifkv_select_topk for context rows)
+ *   n_heads  H_q for query rows, H_kv for key rows (any value > 0)
+ * Errors: IFKV_EINVAL for NULL pointers, negative sizes, misaligned x.
+ */
+int ifkv_rope_rows(ifkv_ctx *ctx, void *x, const int32_t *pos, int64_t n_rows, int32_t n_heads);
+
+/*
  * Optional step before the path -- Method, "Chunk Reordering", Eq. (9).
  *
  * After a first-stage selection (stages 1-3 run with the local-context

@@ -26,7 +26,7 @@ IFKV_FLAG_ATTN_WIDE = 2
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
     "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
-    "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_chunk_counts", "ifkv_reorder_chunks",
+    "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
     "ifkv_copy_bytes",
 )
 
@@ -80,6 +80,8 @@ def load_library() -> C.CDLL:
     lib.ifkv_recompute_attention.restype = C.c_int
     lib.ifkv_splice_kv.argtypes = [vp, vp, vp, vp, i64, vp, vp, i64]
     lib.ifkv_splice_kv.restype = C.c_int
+    lib.ifkv_rope_rows.argtypes = [vp, vp, vp, i64, i32]
+    lib.ifkv_rope_rows.restype = C.c_int
     lib.ifkv_chunk_counts.argtypes = [vp, vp, i64, i32, C.POINTER(i64), i64, vp]
     lib.ifkv_chunk_counts.restype = C.c_int
     lib.ifkv_reorder_chunks.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
@@ -220,6 +222,11 @@ class Layer:
                   k_cache: torch.Tensor, v_cache: Optional[torch.Tensor]) -> None:
         self._check(self._lib.ifkv_splice_kv(self._ctx, _ptr(k_new), _ptr(v_new), _ptr(idx), int(idx.shape[0]),
                                              _ptr(k_cache), _ptr(v_cache), int(k_cache.shape[0])))
+
+    def rope_rows(self, x: torch.Tensor, pos: torch.Tensor) -> torch.Tensor:
+        """In place; x [R, n_heads, d], pos int32 [R]."""
+        self._check(self._lib.ifkv_rope_rows(self._ctx, _ptr(x), _ptr(pos), int(x.shape[0]), int(x.shape[1])))
+        return x
 
     def chunk_counts(self, idx: torch.Tensor, slot_start: Sequence[int], n_ctx: int,
                      counts_out: Optional[torch.Tensor] = None) -> torch.Tensor:

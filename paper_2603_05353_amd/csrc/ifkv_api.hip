@@ -294,6 +294,19 @@ int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new, const in
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "splice kernel launch");
 }
 
+int ifkv_rope_rows(ifkv_ctx *ctx, void *x, const int32_t *pos, int64_t n_rows, int32_t n_heads) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (n_rows < 0 || n_heads <= 0) return fail(ctx, IFKV_EINVAL, "rope_rows: n_rows must be >= 0 and n_heads > 0");
+  if (n_rows >= (int64_t(1) << 31)) return fail(ctx, IFKV_ESHAPE, "rope_rows: too many rows");
+  if (n_rows == 0) return IFKV_OK;
+  if (x == nullptr || pos == nullptr) return fail(ctx, IFKV_EINVAL, "rope_rows: NULL pointer");
+  if (!aligned16(x)) return fail(ctx, IFKV_EINVAL, "rope_rows: x must be 16-byte aligned");
+  int rc = ensure_inv_freq(ctx);
+  if (rc != IFKV_OK) return rc;
+  hipError_t e = ifkv::launch_rope_rows(ctx, x, pos, n_rows, n_heads);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "rope_rows kernel launch");
+}
+
 int ifkv_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, int32_t n_slots, const int64_t *slot_start,
                       int64_t n_ctx, int32_t *counts_out) {
   if (ctx == nullptr) return IFKV_EINVAL;

@@ -228,6 +228,66 @@ __global__ __launch_bounds__(kThreads) void splice_kernel(const v4u *__restrict_
   }
 }
 
+// ---------------------------------------------------------------------------
+// Rotary embedding of recomputed rows -- "KV Recomputation": a selected token is "placed at its
+// global position", so its freshly projected query/key row r is turned by pos[r] * theta_j in
+// every pair j (Eq. 3-4).  One workgroup per row; the first d/2 threads form the row's cos/sin
+// in fp64 (positions reach 1e5: an fp32 angle would be off by 1e-2 rad), the rotation itself is
+// fp32 FMA, rounded once to the storage type.  In place.
+// ---------------------------------------------------------------------------
+template <typename Tag, int PAIRING>
+__global__ __launch_bounds__(kThreads) void rope_rows_kernel(v4u *__restrict__ x, const int32_t *__restrict__ pos,
+                                                             const double *__restrict__ inv_freq, int n_heads,
+                                                             int head_dim) {
+  using E = Elem<Tag>;
+  constexpr int VE = E::kVec;
+  __shared__ float s_cos[kMaxHeadDim / 2];
+  __shared__ float s_sin[kMaxHeadDim / 2];
+  const int tid = threadIdx.x;
+  const int half = head_dim / 2;
+  const int row_vecs = n_heads * head_dim / VE;
+  v4u *row = x + static_cast<int64_t>(blockIdx.x) * row_vecs;
+  if (tid < half) {
+    double sn, cs;
+    sincos(static_cast<double>(pos[blockIdx.x]) * inv_freq[tid], &sn, &cs);
+    s_cos[tid] = static_cast<float>(cs);
+    s_sin[tid] = static_cast<float>(sn);
+  }
+  __syncthreads();
+  if (PAIRING == IFKV_ROPE_HALF) {
+    const int hv = half / VE, hv_shift = __builtin_ctz(hv);
+    for (int it = tid; it < row_vecs / 2; it += kThreads) {
+      const int cc = it & (hv - 1);
+      const int off = ((it >> hv_shift) << (hv_shift + 1)) + cc;
+      float a[VE], b[VE], ra[VE], rb[VE];
+      E::unpack(row[off], a);
+      E::unpack(row[off + hv], b);
+#pragma unroll
+      for (int e = 0; e < VE; ++e) {
+        const float cs = s_cos[cc * VE + e], sn = s_sin[cc * VE + e];
+        ra[e] = fmaf(a[e], cs, -(b[e] * sn));
+        rb[e] = fmaf(a[e], sn, b[e] * cs);
+      }
+      row[off] = E::pack(ra);
+      row[off + hv] = E::pack(rb);
+    }
+  } else {
+    const int head_vecs = head_dim / VE;
+    for (int it = tid; it < row_vecs; it += kThreads) {
+      const int pair0 = (it & (head_vecs - 1)) * (VE / 2);
+      float f[VE], r[VE];
+      E::unpack(row[it], f);
+#pragma unroll
+      for (int e = 0; e < VE / 2; ++e) {
+        const float cs = s_cos[pair0 + e], sn = s_sin[pair0 + e];
+        r[2 * e] = fmaf(f[2 * e], cs, -(f[2 * e + 1] * sn));
+        r[2 * e + 1] = fmaf(f[2 * e], sn, f[2 * e + 1] * cs);
+      }
+      row[it] = E::pack(r);
+    }
+  }
+}
+
 // Plain streaming copy with the same access shape (calibration only).
 __global__ __launch_bounds__(kThreads) void copy_kernel(v4u *__restrict__ dst, const v4u *__restrict__ src,
                                                         int64_t n_vecs) {
@@ -284,6 +344,28 @@ hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, co
   hipLaunchKernelGGL(splice_kernel, grid, block, 0, ctx->stream, reinterpret_cast<const v4u *>(k_new),
                      reinterpret_cast<const v4u *>(v_new), idx, n_rows, row_vecs,
                      reinterpret_cast<v4u *>(k_cache), reinterpret_cast<v4u *>(v_cache), n_kv);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_rows(ifkv_ctx *ctx, void *x, const int32_t *pos, int64_t n_rows, int n_heads) {
+  if (n_rows <= 0 || n_heads <= 0) return hipSuccess;
+  const auto &d = ctx->desc;
+  dim3 grid(static_cast<unsigned>(n_rows)), block(kThreads);
+  v4u *xv = reinterpret_cast<v4u *>(x);
+#define IFKV_LAUNCH_ROPE(TAG, PAIR) \
+  hipLaunchKernelGGL((rope_rows_kernel<TAG, PAIR>), grid, block, 0, ctx->stream, xv, pos, ctx->d_inv_freq, n_heads, d.head_dim)
+  if (d.dtype == IFKV_BF16) {
+    if (d.pairing == IFKV_ROPE_HALF)
+      IFKV_LAUNCH_ROPE(BF16Tag, IFKV_ROPE_HALF);
+    else
+      IFKV_LAUNCH_ROPE(BF16Tag, IFKV_ROPE_INTERLEAVED);
+  } else {
+    if (d.pairing == IFKV_ROPE_HALF)
+      IFKV_LAUNCH_ROPE(F32Tag, IFKV_ROPE_HALF);
+    else
+      IFKV_LAUNCH_ROPE(F32Tag, IFKV_ROPE_INTERLEAVED);
+  }
+#undef IFKV_LAUNCH_ROPE
   return hipGetLastError();
 }
 

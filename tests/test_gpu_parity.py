@@ -484,6 +484,30 @@ def test_composite_layer(cfg, rtol_sel):
 
 
 # ---------------------------------------------------------------------------
+# rotary embedding of recomputed rows
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,pairing,heads", [("C1", "half", 8), ("C2", "half", 32), ("C2", "half", 8),
+                                               ("C2", "interleaved", 32), ("C5", "half", 4), ("C1", "interleaved", 3)])
+def test_rope_rows_parity(cfg, pairing, heads):
+    spec = preset(cfg, pairing=pairing)
+    g = np.random.Generator(np.random.Philox(key=[77, heads]))
+    R, d = 333, spec.head_dim
+    x64 = g.standard_normal((R, heads, d)) * 0.3
+    pos = np.sort(g.choice(140000, size=R, replace=False)).astype(np.int32)
+    pos[0], pos[1] = 0, 1
+    x_st = to_storage(x64, spec.dtype)
+    L = make_layer(spec, max_ctx=1024, max_prompt=8)
+    xd = to_dev(x_st, spec.dtype)
+    L.rope_rows(xd, torch.from_numpy(pos).to(DEV))
+    sync()
+    ref = O.rope_rows(to_f64(x_st, spec.dtype), pos, spec.rope_theta, pairing)
+    got = to_host_f64(xd, spec.dtype)
+    check_reposition(got, ref, spec.dtype, pairing)
+    assert np.array_equal(to_host_bits(xd, spec.dtype)[0], np.ascontiguousarray(x_st[0]).view(np.uint16 if spec.dtype == "bf16" else np.uint32))   # position 0: cos = 1, sin = 0, bit-exact
+    L.close()
+
+
+# ---------------------------------------------------------------------------
 # the other RoPE geometries of the appendix ("RoPE Geometry"), expressed through delta_override
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("geometry", ["HL-TP", "HL-HP", "TL-TP"])
