@@ -14,7 +14,12 @@ Prints ONE JSON line:
              measured with HIP events on the stream the kernels run on
   cpu_baseline  the numpy fp64 oracle timed on this machine's host cores on a
              bounded sample of the same workload
-  stages     per-stage mean time and achieved algorithmic GB/s or TFLOP/s
+  stages     per-stage mean time and achieved algorithmic GB/s or TFLOP/s; for
+             the streaming stages also "cold_ms": the same launch rotating over
+             five buffer sets, so that nothing it touches is still in a cache
+  calibration  what this machine delivers for a plain copy and for a bare MFMA
+             loop (constant operands / operands that switch like activations),
+             to read the fractions of the published peaks against
 """
 import argparse
 import json
@@ -46,7 +51,7 @@ def parse():
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stage-iters", type=int, default=20)
+    ap.add_argument("--stage-iters", type=int, default=30)
     ap.add_argument("--zero-inputs", action="store_true",
                     help="profiling aid for --only recompute_attention: all-zero K, V and queries (same instruction "
                          "stream, least switching activity: shows how far the clock drops on real data)")
@@ -169,10 +174,44 @@ def main():
     t_splice = time_stage(lambda: L.splice_kv(k_new_d, v_new_d, idx_k, K, V), it)
     t_attn = time_stage(lambda: L.recompute_attention(q_sel_d, idx_k, K, V, out=out), it)
 
-    # calibration: what a plain copy of the K+V footprint achieves on this machine
+    # cold-cache variant of the streaming stages: five distinct buffer sets in rotation, so
+    # that a launch finds none of its data in the L2s or the 256 MB memory-side cache
+    n_sets = 5
+    kd_sets = [kd] + [[c.clone() for c in kd] for _ in range(n_sets - 1)]
+    vd_sets = [vd] + [[c.clone() for c in vd] for _ in range(n_sets - 1)]
+    K_sets = [K] + [K.clone() for _ in range(n_sets - 1)]
+    V_sets = [V] + [V.clone() for _ in range(n_sets - 1)]
+    kn_sets = [k_new_d] + [k_new_d.clone() for _ in range(n_sets - 1)]
+    vn_sets = [v_new_d] + [v_new_d.clone() for _ in range(n_sets - 1)]
+    turn = [0]
+
+    def rotating(fn):
+        def call():
+            i = turn[0] % n_sets
+            turn[0] += 1
+            fn(i)
+        return call
+
+    it_cold = max(it, 2 * n_sets)
+    tc_repo = time_stage(rotating(lambda i: L.reposition_keys(kd_sets[i], vd_sets[i], chunk_order=order,
+                                                              k_out=K_sets[i], v_out=V_sets[i])), it_cold)
+    tc_score = time_stage(rotating(lambda i: L.score_tokens(K_sets[i], qd, scores=scores)), it_cold)
+    tc_splice = time_stage(rotating(lambda i: L.splice_kv(kn_sets[i], vn_sets[i], idx_k, K_sets[i], V_sets[i])), it_cold)
+    del kd_sets, vd_sets, K_sets, V_sets, kn_sets, vn_sets
+
+    # calibration: what a plain copy of the K+V footprint achieves on this machine, and what a bare
+    # MFMA loop sustains (about 50 ms per pattern, long enough for the clock to settle)
     src = torch.empty(2 * N * spec.n_kv_heads * spec.head_dim * e, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     t_copy = time_stage(lambda: L.copy_bytes(dst, src), it)
+    del src, dst
+    sink = torch.empty(L.mfma_probe_sink_floats(), dtype=torch.float32, device=dev)
+    probe_iters = 15000
+    probe = {}
+    for name, pattern in (("constant_operands", 0), ("activation_like_operands", 1)):
+        probe_flops = L.mfma_probe(pattern, probe_iters, sink)
+        t_p = time_stage(lambda: L.mfma_probe(pattern, probe_iters, sink), 3)
+        probe[name] = probe_flops / t_p / 1e12
 
     row_bytes = spec.n_kv_heads * spec.head_dim * e
     b_repo = 4 * N * row_bytes                       # K and V, read + write
@@ -188,7 +227,17 @@ def main():
         "splice_kv": {"ms": t_splice * 1e3, "GB/s": b_splice / t_splice / 1e9, "frac_hbm": b_splice / t_splice / HBM_PEAK},
         "recompute_attention": {"ms": t_attn * 1e3, "TFLOP/s": f_attn / t_attn / 1e12,
                                 "frac_mfma": f_attn / t_attn / MFMA_BF16_PEAK},
-        "copy_calibration": {"ms": t_copy * 1e3, "GB/s": 2 * src.numel() / t_copy / 1e9},
+    }
+    stages["reposition_keys"]["cold_ms"] = tc_repo * 1e3
+    stages["score_tokens"]["cold_ms"] = tc_score * 1e3
+    stages["splice_kv"]["cold_ms"] = tc_splice * 1e3
+    t_sum = t_repo + t_score + t_topk + t_splice + t_attn
+    calibration = {
+        "copy": {"ms": t_copy * 1e3, "GB/s": 4 * N * row_bytes / t_copy / 1e9},
+        "mfma_loop_TFLOP/s": probe,
+        "recomputed_tokens_per_s_from_stage_sum": k_sel / t_sum,
+        "context_tokens_per_s_from_stage_sum": N / t_sum,
+        "recomputed_tokens_per_s_attention_only": k_sel / t_attn,
     }
     if spec.dtype == "bf16":
         roofline = {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": f_attn / t_attn / 1e12,
@@ -209,6 +258,7 @@ def main():
                    "ratio": ratio, "n_ctx": N, "k": k_sel},
         "roofline": roofline,
         "stages": stages,
+        "calibration": calibration,
     }
 
     # ---- the oracle on the host cores, bounded sample --------------------------------

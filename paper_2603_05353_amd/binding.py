@@ -27,7 +27,7 @@ EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
     "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
     "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
-    "ifkv_copy_bytes",
+    "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",
 )
 
 
@@ -88,6 +88,10 @@ def load_library() -> C.CDLL:
     lib.ifkv_reorder_chunks.restype = C.c_int
     lib.ifkv_copy_bytes.argtypes = [vp, vp, vp, i64]
     lib.ifkv_copy_bytes.restype = C.c_int
+    lib.ifkv_mfma_probe.argtypes = [vp, i32, i64, vp, C.POINTER(C.c_double)]
+    lib.ifkv_mfma_probe.restype = C.c_int
+    lib.ifkv_mfma_probe_sink_floats.argtypes = []
+    lib.ifkv_mfma_probe_sink_floats.restype = i64
     _lib = lib
     return lib
 
@@ -247,3 +251,17 @@ class Layer:
 
     def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor) -> None:
         self._check(self._lib.ifkv_copy_bytes(self._ctx, _ptr(dst), _ptr(src), src.numel() * src.element_size()))
+
+    def mfma_probe_sink_floats(self) -> int:
+        return int(self._lib.ifkv_mfma_probe_sink_floats())
+
+    def mfma_probe(self, pattern: int, iterations: int, sink: Optional[torch.Tensor] = None) -> float:
+        """Launch the matrix-pipe calibration loop; returns the flops one launch performs."""
+        need = self.mfma_probe_sink_floats()
+        if sink is None:
+            sink = torch.empty(need, dtype=torch.float32, device=self.device)
+        if sink.dtype != torch.float32 or sink.numel() < need:
+            raise ValueError(f"mfma_probe: sink must hold {need} float32")
+        flops = C.c_double(0.0)
+        self._check(self._lib.ifkv_mfma_probe(self._ctx, int(pattern), int(iterations), _ptr(sink), C.byref(flops)))
+        return float(flops.value)

@@ -373,4 +373,16 @@ int ifkv_copy_bytes(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes) 
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "copy kernel launch");
 }
 
+int ifkv_mfma_probe(ifkv_ctx *ctx, int pattern, int64_t iterations, float *sink, double *flops_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (pattern != 0 && pattern != 1) return fail(ctx, IFKV_EINVAL, "mfma_probe: pattern must be 0 or 1");
+  if (iterations < 1 || iterations > 10000000) return fail(ctx, IFKV_EINVAL, "mfma_probe: iterations out of range");
+  if (sink == nullptr) return fail(ctx, IFKV_EINVAL, "mfma_probe: sink is NULL");
+  if (flops_out != nullptr) *flops_out = ifkv::mfma_probe_flops((int)iterations);
+  hipError_t e = ifkv::launch_mfma_probe(ctx, pattern, (int)iterations, sink);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "mfma probe launch");
+}
+
+int64_t ifkv_mfma_probe_sink_floats(void) { return (int64_t)ifkv::mfma_probe_sink_floats(); }
+
 }  // extern "C"

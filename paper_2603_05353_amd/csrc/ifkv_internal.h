@@ -75,6 +75,10 @@ hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, co
 
 // Calibration copy.
 hipError_t launch_copy(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes);
+// matrix-pipe calibration loop (calibrate.hip)
+size_t mfma_probe_sink_floats();
+double mfma_probe_flops(int iters);
+hipError_t launch_mfma_probe(ifkv_ctx *ctx, int pattern, int iters, float *sink);
 
 // Rotary embedding of recomputed rows at given positions, in place.
 hipError_t launch_rope_rows(ifkv_ctx *ctx, void *x, const int32_t *pos, int64_t n_rows, int n_heads);

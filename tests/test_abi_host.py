@@ -185,3 +185,17 @@ def test_reorder_and_counts_reject_bad_arguments(lib):
     rc = lib.ifkv_chunk_counts(L._ctx, None, 0, 2, None, 10, C.cast(out, C.c_void_p))
     assert rc == B.IFKV_EINVAL
     L.close()
+
+
+def test_mfma_probe_rejects_bad_arguments(lib):
+    L = _layer()
+    assert lib.ifkv_mfma_probe_sink_floats() > 0
+    flops = C.c_double(-1.0)
+    fake = C.c_void_p(256)  # never dereferenced: every call below fails validation first
+    assert lib.ifkv_mfma_probe(L._ctx, 2, 10, fake, C.byref(flops)) == B.IFKV_EINVAL
+    assert lib.ifkv_mfma_probe(L._ctx, 0, 0, fake, C.byref(flops)) == B.IFKV_EINVAL
+    assert lib.ifkv_mfma_probe(L._ctx, 0, 10**8, fake, C.byref(flops)) == B.IFKV_EINVAL
+    assert lib.ifkv_mfma_probe(L._ctx, 1, 10, None, C.byref(flops)) == B.IFKV_EINVAL
+    assert lib.ifkv_mfma_probe(None, 1, 10, fake, C.byref(flops)) == B.IFKV_EINVAL
+    assert flops.value == -1.0
+    L.close()

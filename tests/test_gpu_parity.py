@@ -508,6 +508,47 @@ def test_rope_rows_parity(cfg, pairing, heads):
 
 
 # ---------------------------------------------------------------------------
+# prompt rows through the attention stage: the glue a layer's recompute pass needs
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", ["C1", "C2"])
+def test_prompt_rows_and_selected_rows_in_one_attention_call(cfg):
+    """Prompt tokens are always computed fresh ("KV Recomputation"): their keys get rotary positions
+    N..N+M-1 (ifkv_rope_rows), are appended to the spliced cache, and their queries run through the
+    attention stage together with the selected context rows (row_pos beyond N, n_kv = N + M).  Both
+    sides take the stored prompt keys after the rotation, so the attention check is not loosened by it."""
+    spec = preset(cfg, chunk_lens=[210, 97, 160, 133], m_prompt=24)
+    wl = make_workload(spec)
+    N, M = wl.n_ctx, spec.m_prompt
+    K_st, K64, q_prompt64 = global_keys(wl)
+    V_st = np.concatenate([wl.v_chunks[c] for c in wl.chunk_order], axis=0)
+    g = np.random.Generator(np.random.Philox(key=[spec.seed, 31]))
+    kp_raw = to_storage(g.standard_normal((M, spec.n_kv_heads, spec.head_dim)) * spec.sigma, spec.dtype)
+    vp_st = to_storage(g.standard_normal((M, spec.n_kv_heads, spec.head_dim)) * spec.sigma, spec.dtype)
+    sel = sample_rows(N, 90, 3)
+    q_sel, _, _ = make_recompute_inputs(wl, sel)
+    rows = np.concatenate([sel, np.arange(N, N + M)]).astype(np.int64)
+    q_all = np.concatenate([q_sel, to_storage(q_prompt64, spec.dtype)], axis=0)
+
+    L = make_layer(spec, max_ctx=N + M, max_prompt=M)
+    Kd = to_dev(np.concatenate([K_st, kp_raw], axis=0), spec.dtype)
+    Vd = to_dev(np.concatenate([V_st, vp_st], axis=0), spec.dtype)
+    pos_p = torch.arange(N, N + M, dtype=torch.int32, device=DEV)
+    L.rope_rows(Kd[N:], pos_p)                      # in place on the appended rows
+    out, lse = L.recompute_attention(to_dev(q_all, spec.dtype), torch.from_numpy(rows.astype(np.int32)).to(DEV),
+                                     Kd, Vd, return_lse=True)
+    sync()
+    kp_ref = O.rope_rows(to_f64(kp_raw, spec.dtype), np.arange(N, N + M), spec.rope_theta, spec.pairing)
+    check_reposition(to_host_f64(Kd[N:], spec.dtype), kp_ref, spec.dtype, spec.pairing)
+    K_all64 = np.concatenate([K64, to_host_f64(Kd[N:], spec.dtype)], axis=0)
+    V_all64 = np.concatenate([to_f64(V_st, spec.dtype), to_f64(vp_st, spec.dtype)], axis=0)
+    ref, lse_ref = O.recompute_attention(to_f64(q_all, spec.dtype), rows, K_all64, V_all64, wl.sm_scale)
+    tol = 2e-2 if spec.dtype == "bf16" else 1e-4
+    assert np.abs(to_host_f64(out, spec.dtype) - ref).max() <= tol
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref).max() <= tol
+    L.close()
+
+
+# ---------------------------------------------------------------------------
 # the other RoPE geometries of the appendix ("RoPE Geometry"), expressed through delta_override
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("geometry", ["HL-TP", "HL-HP", "TL-TP"])
