@@ -16,6 +16,8 @@
 //           blocks at the end.
 //   pass B: S = Q.K^T, a lane owns one key -> sum over query rows of
 //           exp2(S*c - b_q) with b_q = log2-domain max + log2 Z, in-lane.
+#include <type_traits>
+
 #include "ifkv_device.h"
 #include "score_common.h"
 
@@ -41,6 +43,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct ScoreGeom {
   int n_ctx, m_prompt, n_q_heads, n_kv_heads;
   int n_qchunks;   // query-row chunks per kv head
+  int q_chunk_rows;  // rows per chunk (multiple of 128, <= kQChunk); the last chunk may hold fewer
   int kv_per_block;
   float scale_log2;
 };
@@ -49,36 +52,46 @@ struct ScoreGeom {
 __device__ __forceinline__ bool q_row_address(const ScoreGeom &gm, int g, int qc, int ql, int64_t *off, int *h,
                                               int *r) {
   const int G = gm.n_q_heads / gm.n_kv_heads;
-  const int qi = qc * kQChunk + ql;
+  const int qi = qc * gm.q_chunk_rows + ql;
   *r = qi / G;
   *h = g * G + (qi - *r * G);
   *off = (static_cast<int64_t>(*r) * gm.n_q_heads + *h) * D;
   return qi < gm.m_prompt * G;
 }
 
-__device__ __forceinline__ void load_q_chunk(uint16_t *q_lds, const uint16_t *__restrict__ q_prompt,
-                                             const ScoreGeom &gm, int g, int qc, int rows) {
-  // eight independent 16-byte loads per thread are in flight before the first LDS store
-  constexpr int kInFlight = 8;
-  const int total = rows * (D / 8);
-  for (int v0 = threadIdx.x; v0 < total; v0 += kThreads * kInFlight) {
-    v4u x[kInFlight];
+// Staging of a kv head's query tile (NV * 32 rows, NV = 4, 8, 12 or 16; rows past the real ones are
+// zero) in two halves, so that the caller can put other requests between them: q_tile_request issues
+// all of a thread's 16-byte loads (NV of them, rows 32 apart: the row -> (prompt row, head) split
+// needs one division, the rest is incremental), q_tile_store writes them to LDS.
+template <int NV>
+__device__ __forceinline__ void q_tile_request(v4u (&x)[NV], const uint16_t *__restrict__ q_prompt,
+                                               const ScoreGeom &gm, int g, int qc) {
+  const int G = gm.n_q_heads / gm.n_kv_heads;
+  const int total = gm.m_prompt * G;
+  const int c = threadIdx.x & 15;
+  int qi = qc * gm.q_chunk_rows + (threadIdx.x >> 4);
+  int r = qi / G, hg = qi - r * G;
+  const int dr = 32 / G, dh = 32 - dr * G;
 #pragma unroll
-    for (int u = 0; u < kInFlight; ++u) {
-      const int v = v0 + u * kThreads;
-      const int ql = v >> 4, c = v & 15;
-      int64_t off;
-      int h, r;
-      x[u] = v4u{0u, 0u, 0u, 0u};
-      if (v < total && q_row_address(gm, g, qc, ql, &off, &h, &r))
-        x[u] = *reinterpret_cast<const v4u *>(q_prompt + off + 8 * c);
-    }
-#pragma unroll
-    for (int u = 0; u < kInFlight; ++u) {
-      const int v = v0 + u * kThreads;
-      if (v < total) *reinterpret_cast<v4u *>(&q_lds[(v >> 4) * QSTR + 8 * (v & 15)]) = x[u];
+  for (int u = 0; u < NV; ++u) {
+    x[u] = v4u{0u, 0u, 0u, 0u};
+    if (qi < total)
+      x[u] = *reinterpret_cast<const v4u *>(q_prompt + (static_cast<int64_t>(r) * gm.n_q_heads + g * G + hg) * D +
+                                            8 * c);
+    qi += 32;
+    r += dr;
+    hg += dh;
+    if (hg >= G) {
+      hg -= G;
+      ++r;
     }
   }
+}
+template <int NV>
+__device__ __forceinline__ void q_tile_store(uint16_t *q_lds, const v4u (&x)[NV]) {
+  const int c = threadIdx.x & 15, ql = threadIdx.x >> 4;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) *reinterpret_cast<v4u *>(&q_lds[(ql + 32 * u) * QSTR + 8 * c]) = x[u];
 }
 
 // K fragments of one 64-key tile in MFMA operand layout: lane (row, hf) holds
@@ -135,48 +148,70 @@ __device__ __forceinline__ void qk_block(f32x16 &S0, f32x16 &S1, const bf16x8 (&
 // ---------------------------------------------------------------------------
 // pass A
 // ---------------------------------------------------------------------------
+// Pass A for blocks whose query rows fill NQB 32-row blocks (NQB even; rows past the real ones are
+// zero in LDS and their statistics are never written).  NQB is a compile-time constant so that a
+// tile is one straight run of code: the software pipeline below relies on scheduling fences, which
+// order instructions only within a basic block.  With a run-time block count the compiler hoisted
+// all MFMAs of a tile above the vector work of its first block and moved the vector work of one
+// step behind the MFMAs of the next.
+template <int NQB>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, kWpe))) void score_stats_mfma(
     const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm,
     float2 *__restrict__ partial) {
-  __shared__ __attribute__((aligned(16))) uint16_t q_lds[kQChunk * QSTR];
-  const int G = gm.n_q_heads / gm.n_kv_heads;
+  __shared__ __attribute__((aligned(16))) uint16_t q_lds[NQB * 32 * QSTR];
   const int kb = blockIdx.x;
   const int g = blockIdx.y / gm.n_qchunks;
   const int qc = blockIdx.y - g * gm.n_qchunks;
-  const int q_total = gm.m_prompt * G;
-  const int q_rows = min(kQChunk, q_total - qc * kQChunk);
-  const int nqb = ((q_rows + 63) >> 6) << 1;  // 32-row query blocks, padded to an even count
+  const int G = gm.n_q_heads / gm.n_kv_heads;
+  const int q_rows = min(gm.q_chunk_rows, gm.m_prompt * G - qc * gm.q_chunk_rows);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, hf = lane >> 5;
 
   const float c = gm.scale_log2;
   const int kv_begin = kb * gm.kv_per_block;
   const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
-  // the first key tile is requested before the query tile is staged, so both travel together
+  // the query tile and the first key tile are requested together, before anything waits
   bf16x8 kf[2][8];
   int j0 = kv_begin + wave * kTile;
-  if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
-
-  load_q_chunk(q_lds, q_prompt, gm, g, qc, nqb * 32);
+  {
+    v4u qx[NQB];
+    q_tile_request<NQB>(qx, q_prompt, gm, g, qc);
+    if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
+    q_tile_store<NQB>(q_lds, qx);
+  }
   __syncthreads();
 
-  float m[kQBlocks], z[kQBlocks];
+  // This lane's row in the lower and in the upper eight query blocks.  From one base the byte offsets
+  // of the far blocks exceed the 16-bit immediate of an LDS read, and the compiler then keeps a
+  // separate address register per fragment (22 of them, spilled); the empty asm hides that the
+  // second base is a constant away from the first.
+  typedef __attribute__((address_space(3))) const v4u lds_v4u;
+  lds_v4u *q_lo = (lds_v4u *)(q_lds + row * QSTR + 8 * hf);
+  lds_v4u *q_hi = (lds_v4u *)(q_lds + ((NQB > 8 ? 8 * 32 : 0) + row) * QSTR + 8 * hf);
+  asm volatile("" : "+v"(q_hi));
+  auto q_frag_a = [&](int qb, int s) {
+    lds_v4u *base = qb < 8 ? q_lo : q_hi;
+    return __builtin_bit_cast(bf16x8, base[((qb & 7) * 32 * QSTR + 16 * s) / 8]);
+  };
+
+  float m[NQB], z[NQB];
 #pragma unroll
-  for (int qb = 0; qb < kQBlocks; ++qb) {
+  for (int qb = 0; qb < NQB; ++qb) {
     m[qb] = -INFINITY;
     z[qb] = 0.f;
   }
   // register r of S_t: key j0 + 32 t + 8 (r/4) + 4 hf + r%4, query row qb*32 + (lane & 31)
   //
-  // Software pipeline over the query blocks (their count is even).  pipe_step issues the sixteen
-  // MFMAs of block qn into (N0, N1) in eight slices of two; each slice is followed by a share of
-  // the vector work on the finished block (C0, C1): slice 0 takes the running maximum, slices
-  // 1..7 the exponentials and the sum.  The fences keep the slices in this order, so the matrix
-  // pipe works underneath the vector instructions of the same wavefront.  The last step of a
-  // tile issues one block whose products are not used.
-  auto pipe_step = [&](const bf16x8 (&kf)[2][8], f32x16 &N0, f32x16 &N1, int qn, f32x16 &C0, f32x16 &C1, float &mq,
-                       float &zq, int j0, bool tail) {
-    if (tail) {  // ragged last tile only
+  // Software pipeline over the query blocks.  pipe_step issues the sixteen MFMAs of block qn into
+  // (N0, N1) in eight slices of two; each slice is followed by a share of the vector work on the
+  // finished block (C0, C1): slice 0 takes the running maximum, slices 1..7 the exponentials and
+  // the sum.  The fences keep the slices in this order, so the matrix pipe works underneath the
+  // vector instructions of the same wavefront.  The last step of a tile issues one block whose
+  // products are not used.  tail_tag (a compile-time tag, for the same reason as NQB) selects the
+  // variant for a ragged last tile, which masks the keys past the end.
+  auto pipe_step = [&](auto tail_tag, f32x16 &N0, f32x16 &N1, int qn, f32x16 &C0, f32x16 &C1, float &mq, float &zq,
+                       int j0) {
+    if (decltype(tail_tag)::value) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int kv = j0 + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -185,26 +220,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
       }
     }
     float m_use = 0.f, m_new = 0.f, acc = 0.f;
-    bf16x8 qf = q_frag(q_lds, qn, 0, row, hf);
+    bf16x8 qf = q_frag_a(qn, 0);
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       bf16x8 qf_next = qf;
-      if (s < 7) qf_next = q_frag(q_lds, qn, s + 1, row, hf);
+      if (s < 7) qf_next = q_frag_a(qn, s + 1);
       qk_step<true>(N0, N1, kf, qf, s);
+      // The empty asm statements tie the vector work to its slice: they are ordered against the
+      // fences, the values that pass through them cannot be formed earlier or used later, so the
+      // instruction selector cannot collect the vector work of all slices behind the last MFMA.
       if (s == 0) {
         float mx = C0[0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, fmaxf(C0[r], C1[r]));
+        for (int r = 0; r < 16; ++r) mx = fmaxf(fmaxf(mx, C0[r]), C1[r]);  // chain form: one v_max3 per pair
         m_new = fmaxf(mq, mx * c);
         m_use = fmaxf(m_new, -1e30f);  // a lane that has seen no valid key yet stays at (-inf, 0)
+        asm volatile("" : "+v"(m_use));
       } else {
         // 32 values over seven slices: registers [lo, hi) of both halves
         const int lo = ((s - 1) * 16) / 7, hi = (s * 16) / 7;
+        asm volatile("" : "+v"(m_use));
 #pragma unroll
         for (int r = lo; r < hi; ++r) {
           acc += __builtin_amdgcn_exp2f(fmaf(C0[r], c, -m_use));
           acc += __builtin_amdgcn_exp2f(fmaf(C1[r], c, -m_use));
         }
+        asm volatile("" : "+v"(acc));
       }
       __builtin_amdgcn_sched_barrier(0);
       qf = qf_next;
@@ -212,17 +253,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
     zq = zq * __builtin_amdgcn_exp2f(mq - m_use) + acc;
     mq = m_new;
   };
-  for (; j0 < kv_end; j0 += kWaves * kTile) {
-    const bool tail = j0 + kTile > kv_end;
+  auto tile = [&](auto tail_tag, int j0) {
     f32x16 A0, A1, B0, B1;
-    qk_block<true>(A0, A1, kf, q_lds, 0, row, hf);
 #pragma unroll
-    for (int qb = 0; qb < kQBlocks; qb += 2) {
-      if (qb < nqb) {
-        pipe_step(kf, B0, B1, qb + 1, A0, A1, m[qb], z[qb], j0, tail);
-        pipe_step(kf, A0, A1, min(qb + 2, nqb - 1), B0, B1, m[qb + 1], z[qb + 1], j0, tail);
-      }
+    for (int s = 0; s < 8; ++s) qk_step<true>(A0, A1, kf, q_frag_a(0, s), s);  // block 0, nothing interleaved
+#pragma unroll
+    for (int qb = 0; qb < NQB; qb += 2) {
+      pipe_step(tail_tag, B0, B1, qb + 1, A0, A1, m[qb], z[qb], j0);
+      pipe_step(tail_tag, A0, A1, qb + 2 < NQB ? qb + 2 : NQB - 1, B0, B1, m[qb + 1], z[qb + 1], j0);
     }
+  };
+  for (; j0 < kv_end; j0 += kWaves * kTile) {
+    if (j0 + kTile > kv_end)
+      tile(std::true_type{}, j0);
+    else
+      tile(std::false_type{}, j0);
     const int j_next = j0 + kWaves * kTile;
     if (j_next < kv_end) load_k_frags(kf, k_global, gm, g, j_next, row, hf);
   }
@@ -230,24 +275,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
   // merge the two lane halves (same query row, disjoint keys), then the wavefronts
   __syncthreads();
   // every wavefront is done with the query tile: LDS is reused below
-  float2 *w_stats = reinterpret_cast<float2 *>(q_lds);  // [kWaves][kQChunk]
+  float2 *w_stats = reinterpret_cast<float2 *>(q_lds);  // [kWaves][NQB * 32]
 #pragma unroll
-  for (int qb = 0; qb < kQBlocks; ++qb) {
-    if (qb < nqb) {
-      const float mo = __shfl_xor(m[qb], 32, 64);
-      const float zo = __shfl_xor(z[qb], 32, 64);
-      const float mm = fmaxf(m[qb], mo);
-      const float mu = fmaxf(mm, -1e30f);
-      const float zz = z[qb] * __builtin_amdgcn_exp2f(m[qb] - mu) + zo * __builtin_amdgcn_exp2f(mo - mu);
-      if (hf == 0) w_stats[wave * kQChunk + qb * 32 + row] = make_float2(mm, zz);
-    }
+  for (int qb = 0; qb < NQB; ++qb) {
+    const float mo = __shfl_xor(m[qb], 32, 64);
+    const float zo = __shfl_xor(z[qb], 32, 64);
+    const float mm = fmaxf(m[qb], mo);
+    const float mu = fmaxf(mm, -1e30f);
+    const float zz = z[qb] * __builtin_amdgcn_exp2f(m[qb] - mu) + zo * __builtin_amdgcn_exp2f(mo - mu);
+    if (hf == 0) w_stats[wave * (NQB * 32) + qb * 32 + row] = make_float2(mm, zz);
   }
   __syncthreads();
   for (int ql = threadIdx.x; ql < q_rows; ql += kThreads) {
     float mm = -INFINITY, zz = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      const float2 p = w_stats[w * kQChunk + ql];
+      const float2 p = w_stats[w * (NQB * 32) + ql];
       const float mn = fmaxf(mm, p.x);
       const float mu = fmaxf(mn, -1e30f);
       zz = zz * __builtin_amdgcn_exp2f(mm - mu) + p.y * __builtin_amdgcn_exp2f(p.x - mu);
@@ -274,19 +317,29 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
   const int g = blockIdx.y / gm.n_qchunks;
   const int qc = blockIdx.y - g * gm.n_qchunks;
   const int q_total = gm.m_prompt * G;
-  const int q_rows = min(kQChunk, q_total - qc * kQChunk);
+  const int q_rows = min(gm.q_chunk_rows, q_total - qc * gm.q_chunk_rows);
   const int nqb = ((q_rows + 63) >> 6) << 1;  // 32-row query blocks, padded to an even count
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, hf = lane >> 5;
   const float c = gm.scale_log2;
   const int kv_begin = kb * gm.kv_per_block;
   const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
-  // the first key tile is requested before the query tile is staged, so both travel together
+  // the query tile and the first key tile are requested together, before anything waits
   bf16x8 kf[2][8];
   int j0 = kv_begin + wave * kTile;
-  if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
-
-  load_q_chunk(q_lds, q_prompt, gm, g, qc, nqb * 32);
+  auto stage_q = [&](auto nv_tag) {
+    constexpr int NV = decltype(nv_tag)::value;
+    v4u qx[NV];
+    q_tile_request<NV>(qx, q_prompt, gm, g, qc);
+    if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
+    q_tile_store<NV>(q_lds, qx);
+  };
+  switch (gm.q_chunk_rows >> 7) {  // uniform over the grid
+    case 1: stage_q(std::integral_constant<int, 4>{}); break;
+    case 2: stage_q(std::integral_constant<int, 8>{}); break;
+    case 3: stage_q(std::integral_constant<int, 12>{}); break;
+    default: stage_q(std::integral_constant<int, 16>{}); break;
+  }
   for (int ql = threadIdx.x; ql < nqb * 32; ql += kThreads) {
     int64_t off;
     int h, r;
@@ -362,7 +415,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) kf[t][s2] = kf_next[t][s2];
     }
-    col0 += __shfl_xor(col0, 32, 64);
+      col0 += __shfl_xor(col0, 32, 64);
     col1 += __shfl_xor(col1, 32, 64);
     if (hf == 0) {
       if (j0 + row < kv_end) dst[j0 + row] = col0;
@@ -400,7 +453,10 @@ hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t
   gm.m_prompt = m_prompt;
   gm.n_q_heads = d.n_q_heads;
   gm.n_kv_heads = d.n_kv_heads;
+  // query rows of a kv head are cut into equal chunks of a multiple of 128 rows (pass A is compiled
+  // for 4, 8, 12 and 16 blocks of 32 rows)
   gm.n_qchunks = (m_prompt * G + kQChunk - 1) / kQChunk;
+  gm.q_chunk_rows = ((m_prompt * G + gm.n_qchunks - 1) / gm.n_qchunks + 127) / 128 * 128;
   gm.scale_log2 = ctx->sm_scale * kLog2e;
   // one block per CU when the context is long enough; a block owns whole 64-key tiles
   const int per_head = d.n_kv_heads * gm.n_qchunks;
@@ -421,8 +477,14 @@ hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t
   float *colpart = reinterpret_cast<float *>(base + sc.colpart_off);
   dim3 grid(kv_blocks, per_head);
   if (!pass_b) {
-    hipLaunchKernelGGL(score_stats_mfma, grid, dim3(kThreads), 0, ctx->stream,
-                       static_cast<const uint16_t *>(k_global), static_cast<const uint16_t *>(q_prompt), gm, partial);
+    const auto *kg = static_cast<const uint16_t *>(k_global);
+    const auto *qp = static_cast<const uint16_t *>(q_prompt);
+    switch (gm.q_chunk_rows / 128) {
+      case 1: hipLaunchKernelGGL(score_stats_mfma<4>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
+      case 2: hipLaunchKernelGGL(score_stats_mfma<8>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
+      case 3: hipLaunchKernelGGL(score_stats_mfma<12>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
+      default: hipLaunchKernelGGL(score_stats_mfma<16>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
+    }
   } else {
     hipLaunchKernelGGL(score_colsum_mfma, grid, dim3(kThreads), 0, ctx->stream,
                        static_cast<const uint16_t *>(k_global), static_cast<const uint16_t *>(q_prompt), gm, stats,
