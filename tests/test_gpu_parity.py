@@ -447,9 +447,36 @@ def run_layer_gpu(wl, ratio, flags=0):
 def test_composite_layer(cfg, rtol_sel):
     """Whole path, in the order: reposition, score, select, splice, attend."""
     spec = preset(cfg) if cfg == "C1" else preset("C2", chunk_lens=[256] * 6, m_prompt=32)
+    composite_case(spec, 0.15, rtol_sel)
+
+
+def random_shape_spec(seed):
+    """A seeded odd-shaped layer: head counts, group sizes, head_dim, chunk lengths (one of them may be
+    empty), prompt length and chunk order all drawn, to reach the ragged paths of every kernel."""
+    g = np.random.Generator(np.random.Philox(key=[seed, 99]))
+    dtype = "f32" if seed % 4 == 0 else "bf16"
+    d = 64 if (dtype == "f32" or seed % 3 == 0) else 128
+    h_kv = int(g.choice([1, 2, 4, 8]))
+    grp = int(g.choice([1, 2, 3, 4, 7, 8]))
+    lens = [int(x) for x in g.integers(1, 230, size=int(g.integers(1, 8)))]
+    if len(lens) > 2 and seed % 2:
+        lens[1] = 0
+    base = "C1" if dtype == "f32" else "C2"
+    spec = preset(base, n_q_heads=h_kv * grp, n_kv_heads=h_kv, head_dim=d, chunk_lens=lens,
+                  m_prompt=int(g.integers(1, 41)), permute_order=True, seed=20260305 + 100 + seed,
+                  sigma=1.0 if dtype == "f32" else float(d) ** -0.5)
+    return spec, float(g.choice([0.05, 0.15, 0.3, 0.5]))
+
+
+@pytest.mark.parametrize("seed", list(range(1, 13)))
+def test_composite_layer_random_shapes(seed):
+    spec, ratio = random_shape_spec(seed)
+    composite_case(spec, ratio, 1e-5 if spec.dtype == "f32" else 1e-4)
+
+
+def composite_case(spec, ratio, rtol_sel):
     wl = make_workload(spec)
     k, v, q = oracle_inputs(wl)
-    ratio = 0.15
     L, K, V, s, idx = run_layer_gpu(wl, ratio)
     # oracle on its own
     Kref, Vref, _, N = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, spec.pairing)
