@@ -18,10 +18,10 @@ namespace ifkv {
 
 namespace {
 
-constexpr int kStatThreads = 128;  // one prompt row per thread
+constexpr int kStatThreads = 64;   // one prompt row per thread
 constexpr int kStatTile = 32;      // context tokens staged in LDS per step
 
-// Pass A: partial (m, Z) of one slice of the context for 128 prompt rows of one head.
+// Pass A: partial (m, Z) of one slice of the context for 64 prompt rows of one head.
 template <typename Tag, int D>
 __global__ __launch_bounds__(kStatThreads) void score_stats_generic(const void *__restrict__ k_global, int64_t n_ctx,
                                                                     const void *__restrict__ q_prompt, int m_prompt,
@@ -118,57 +118,67 @@ __global__ __launch_bounds__(64) void score_merge_kernel(const float2 *__restric
   stats[h * m_prompt + r] = make_float2(m, z > 0.f ? 1.f / z : 0.f);
 }
 
-constexpr int kColThreads = 256;  // one context token per thread
+constexpr int kColThreads = 128;  // one context token per thread
 constexpr int kColRows = 32;      // prompt rows staged in LDS per step
 
-// Pass B: column sums with the final (m, 1/Z).
+// Pass B: column sums with the final (m, 1/Z).  A block owns 128 context tokens of ONE kv head (its
+// key rows stay in registers) and sums over that head's G query heads and all prompt rows; the
+// per-kv-head partial sums are added up by score_colsum_reduce (no float atomics: the result does not
+// depend on the order in which blocks finish).
 template <typename Tag, int D>
 __global__ __launch_bounds__(kColThreads) void score_colsum_generic(const void *__restrict__ k_global, int64_t n_ctx,
                                                                     const void *__restrict__ q_prompt, int m_prompt,
                                                                     int n_q_heads, int n_kv_heads, float sm_scale,
-                                                                    const float2 *__restrict__ stats, int accumulate,
-                                                                    float *__restrict__ scores) {
+                                                                    const float2 *__restrict__ stats,
+                                                                    float *__restrict__ colpart) {
   using E = Elem<Tag>;
   __shared__ float qs[kColRows][D];
   __shared__ float2 st[kColRows];
   const int64_t j = static_cast<int64_t>(blockIdx.x) * kColThreads + threadIdx.x;
   const bool active = j < n_ctx;
   const int G = n_q_heads / n_kv_heads;
+  const int g = blockIdx.y;
   float acc = 0.f;
-  for (int g = 0; g < n_kv_heads; ++g) {
-    float kreg[D];
-    if (active) {
-      const int64_t koff = (j * n_kv_heads + g) * D;
+  float kreg[D];
+  if (active) {
+    const int64_t koff = (j * n_kv_heads + g) * D;
 #pragma unroll
-      for (int c = 0; c < D; ++c) kreg[c] = E::load1(k_global, koff + c);
-    } else {
+    for (int c = 0; c < D; ++c) kreg[c] = E::load1(k_global, koff + c);
+  } else {
 #pragma unroll
-      for (int c = 0; c < D; ++c) kreg[c] = 0.f;
-    }
-    for (int hh = 0; hh < G; ++hh) {
-      const int h = g * G + hh;
-      for (int r0 = 0; r0 < m_prompt; r0 += kColRows) {
-        const int nr = min(kColRows, m_prompt - r0);
-        __syncthreads();
-        for (int e = threadIdx.x; e < nr * D; e += kColThreads) {
-          const int rr = e / D, c = e - rr * D;
-          qs[rr][c] = E::load1(q_prompt, (static_cast<int64_t>(r0 + rr) * n_q_heads + h) * D + c) * sm_scale;
-        }
-        if (threadIdx.x < nr) st[threadIdx.x] = stats[h * m_prompt + r0 + threadIdx.x];
-        __syncthreads();
-        for (int rr = 0; rr < nr; ++rr) {
-          float dot = 0.f;
+    for (int c = 0; c < D; ++c) kreg[c] = 0.f;
+  }
+  for (int hh = 0; hh < G; ++hh) {
+    const int h = g * G + hh;
+    for (int r0 = 0; r0 < m_prompt; r0 += kColRows) {
+      const int nr = min(kColRows, m_prompt - r0);
+      __syncthreads();
+      for (int e = threadIdx.x; e < nr * D; e += kColThreads) {
+        const int rr = e / D, c = e - rr * D;
+        qs[rr][c] = E::load1(q_prompt, (static_cast<int64_t>(r0 + rr) * n_q_heads + h) * D + c) * sm_scale;
+      }
+      if (threadIdx.x < nr) st[threadIdx.x] = stats[h * m_prompt + r0 + threadIdx.x];
+      __syncthreads();
+      for (int rr = 0; rr < nr; ++rr) {
+        float dot = 0.f;
 #pragma unroll
-          for (int c = 0; c < D; ++c) dot = fmaf(qs[rr][c], kreg[c], dot);
-          acc += expf(dot - st[rr].x) * st[rr].y;
-        }
+        for (int c = 0; c < D; ++c) dot = fmaf(qs[rr][c], kreg[c], dot);
+        acc += expf(dot - st[rr].x) * st[rr].y;
       }
     }
   }
-  if (active) {
-    const float v = acc / static_cast<float>(n_q_heads);
-    scores[j] = accumulate ? scores[j] + v : v;
-  }
+  if (active) colpart[static_cast<int64_t>(g) * n_ctx + j] = acc;
+}
+
+// scores[j] = (accumulate ? scores[j] : 0) + (1 / H_q) * sum over kv heads of the partial column sums
+__global__ void score_colsum_reduce(const float *__restrict__ colpart, int n_parts, int64_t n_ctx, float inv_heads,
+                                    int accumulate, float *__restrict__ scores) {
+  const int64_t j = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (j >= n_ctx) return;
+  float s = 0.f;
+  for (int p = 0; p < n_parts; ++p) s += colpart[static_cast<int64_t>(p) * n_ctx + j];
+  s *= inv_heads;
+  scores[j] = accumulate ? scores[j] + s : s;
 }
 
 __global__ void fill_zero_kernel(float *p, int64_t n) {
@@ -180,7 +190,7 @@ int slice_len_for(int64_t n_ctx) {
   // at most 64 slices, each a multiple of the LDS tile
   int64_t sl = (n_ctx + 63) / 64;
   sl = ((sl + kStatTile - 1) / kStatTile) * kStatTile;
-  if (sl < 128) sl = 128;
+  if (sl < 64) sl = 64;
   return static_cast<int>(sl);
 }
 
@@ -200,9 +210,13 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const
   const int rows = d.n_q_heads * m_prompt;
   hipLaunchKernelGGL((score_merge_kernel<Tag, D>), dim3((rows + 63) / 64), dim3(64), 0, st, partial, n_slices,
                      q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
-  hipLaunchKernelGGL((score_colsum_generic<Tag, D>), dim3(static_cast<unsigned>((n_ctx + kColThreads - 1) / kColThreads)),
+  float *colpart = reinterpret_cast<float *>(static_cast<char *>(ctx->scratch) + sc.colpart_off);
+  hipLaunchKernelGGL((score_colsum_generic<Tag, D>),
+                     dim3(static_cast<unsigned>((n_ctx + kColThreads - 1) / kColThreads), d.n_kv_heads),
                      dim3(kColThreads), 0, st, k_global, n_ctx, q_prompt, m_prompt, d.n_q_heads, d.n_kv_heads,
-                     ctx->sm_scale, stats, accumulate, scores);
+                     ctx->sm_scale, stats, colpart);
+  hipLaunchKernelGGL(score_colsum_reduce, dim3(static_cast<unsigned>((n_ctx + 255) / 256)), dim3(256), 0, st, colpart,
+                     d.n_kv_heads, n_ctx, 1.0f / d.n_q_heads, accumulate, scores);
   return hipGetLastError();
 }
 
