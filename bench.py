@@ -40,7 +40,7 @@ MFMA_BF16_PEAK = 2.5e15  # flop/s, dense bf16
 # runs, scaled by what the same counters read for the plain copy kernel
 # (profiles/attn_mfma_kernel_C3_ratio015_counters.md); None for workloads that
 # were not profiled.
-ATTENTION_TRAFFIC_BYTES = {("C3", 0.15): 8.794e8}
+ATTENTION_TRAFFIC_BYTES = {("C3", 0.15): 8.568e8}
 
 
 def parse():
