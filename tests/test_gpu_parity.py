@@ -179,6 +179,32 @@ def test_score_parity(name, spec, flags, rtol):
     L.close()
 
 
+# (context lengths, prompt rows, H_q, H_kv): every compiled query-block count of pass A (4, 8, 12, 16),
+# several query chunks per kv head, the largest prompt the MFMA path takes (M G = 2048) and the first
+# one it hands to the ALU path, and contexts shorter than one key tile
+SCORE_SHAPES = [
+    ([1], 3, 8, 2), ([63], 32, 8, 2), ([65, 64], 64, 8, 2), ([100, 93], 96, 8, 2), ([70, 121], 128, 8, 2),
+    ([150], 130, 8, 2), ([90, 45], 257, 8, 2), ([77], 512, 8, 2), ([77], 513, 8, 2), ([200], 96, 28, 4),
+    ([129], 40, 32, 1),
+]
+
+
+@pytest.mark.parametrize("lens,m,hq,hkv", SCORE_SHAPES, ids=[f"N{sum(c[0])}-M{c[1]}-{c[2]}q{c[3]}kv" for c in SCORE_SHAPES])
+def test_score_mfma_shapes(lens, m, hq, hkv):
+    spec = preset("C2", chunk_lens=lens, m_prompt=m, n_q_heads=hq, n_kv_heads=hkv, seed=20260305 + 50 + m)
+    wl = make_workload(spec)
+    K_st, K64, q64 = global_keys(wl)
+    s_ref = O.score_tokens(K64, q64, wl.sm_scale)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=m)
+    s = L.score_tokens(to_dev(K_st, spec.dtype), to_dev(wl.q_prompt, spec.dtype))
+    sync()
+    s = s.cpu().numpy().astype(np.float64)
+    assert (np.abs(s - s_ref) <= score_tol(s_ref, m, 1e-2)).all(), \
+        f"max rel {np.max(np.abs(s - s_ref) / (np.abs(s_ref) + m / wl.n_ctx))}"
+    assert abs(s.sum() - m) < 1e-3 * m
+    L.close()
+
+
 @pytest.mark.parametrize("flags", [0, FORCE_GENERIC], ids=["default", "alu"])
 def test_score_with_prompt_keys(flags):
     spec = preset("C2", chunk_lens=[90, 41], m_prompt=12)
@@ -330,6 +356,29 @@ def test_attention_parity_bf16(name, spec, k, flags):
         out, lse, ref, lse_ref = attention_case_subsampled(spec, rows, 300, flags=flags)
     else:
         out, lse, ref, lse_ref = attention_case(spec, rows, flags=flags)
+    assert np.abs(out - ref).max() <= 2e-2, np.abs(out - ref).max()
+    assert np.abs(lse - lse_ref).max() <= 2e-2
+
+
+# (chunk lengths, selected rows or a count to draw, H_q, H_kv): caches shorter than / equal to / one past a
+# key tile, a single row, every row, the largest and the smallest group size the MFMA path takes
+ATTN_SHAPES = [
+    ([1], [0], 8, 2), ([63], "all", 8, 2), ([64], [0, 63], 8, 2), ([65], [64], 8, 2), ([65], "all", 8, 2),
+    ([128, 100], 50, 32, 1), ([300], 200, 8, 8), ([129], [0, 1, 2, 127, 128], 28, 4),
+]
+
+
+@pytest.mark.parametrize("lens,rows,hq,hkv", ATTN_SHAPES,
+                         ids=[f"N{sum(c[0])}-{c[1] if not isinstance(c[1], list) else len(c[1])}rows-{c[2]}q{c[3]}kv" for c in ATTN_SHAPES])
+@pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
+def test_attention_mfma_shapes(lens, rows, hq, hkv, flags):
+    spec = preset("C2", chunk_lens=lens, m_prompt=8, n_q_heads=hq, n_kv_heads=hkv)
+    n_ctx = sum(lens)
+    if rows == "all":
+        rows = np.arange(n_ctx)
+    elif isinstance(rows, int):
+        rows = sample_rows(n_ctx, rows, 4)
+    out, lse, ref, lse_ref = attention_case(spec, np.asarray(rows, dtype=np.int64), flags=flags)
     assert np.abs(out - ref).max() <= 2e-2, np.abs(out - ref).max()
     assert np.abs(lse - lse_ref).max() <= 2e-2
 
