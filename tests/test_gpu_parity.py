@@ -499,6 +499,54 @@ def test_composite_layer(cfg, rtol_sel):
     composite_case(spec, 0.15, rtol_sel)
 
 
+@pytest.mark.parametrize("cfg", ["C1", "C2"])
+def test_step_replays_from_a_captured_graph(cfg):
+    """All five stages enqueue on the stream the layer was created on, allocate nothing once their
+    scratch exists and use no memset, so a caller can capture a whole step into a graph.  Every replay
+    (with eager work and synchronisations in between) must reproduce the eager step bit for bit."""
+    spec = preset(cfg) if cfg == "C1" else preset("C2", chunk_lens=[300, 211, 170, 256], m_prompt=32, permute_order=True)
+    wl = make_workload(spec)
+    ratio = 0.15
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=spec.m_prompt)   # binds the current stream
+        kd, vd = dev_chunks(wl)
+        qd = to_dev(wl.q_prompt, spec.dtype)
+        order = wl.chunk_order.tolist()
+        K, V, _, N = L.reposition_keys(kd, vd, chunk_order=order)
+        scores = L.score_tokens(K, qd)
+        idx = L.select_topk(scores, ratio=ratio)
+        side.synchronize()
+        q_sel, k_new, v_new = make_recompute_inputs(wl, idx.cpu().numpy().astype(np.int64))
+        qs, kn, vn = to_dev(q_sel, spec.dtype), to_dev(k_new, spec.dtype), to_dev(v_new, spec.dtype)
+        out = torch.empty_like(qs)
+
+        def step():
+            L.reposition_keys(kd, vd, chunk_order=order, k_out=K, v_out=V)
+            L.score_tokens(K, qd, scores=scores)
+            L.select_topk(scores, ratio=ratio, idx_out=idx)
+            L.splice_kv(kn, vn, idx, K, V)
+            L.recompute_attention(qs, idx, K, V, out=out)
+
+        step()       # eager: also sizes every scratch buffer
+        step()
+        side.synchronize()
+        want = [t.clone() for t in (K, V, scores, idx, out)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for _ in range(3):
+        for t in (K, V, scores, out):
+            t.zero_()
+        idx.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((K, V, scores, idx, out), want):
+            assert torch.equal(got, ref)
+    L.close()
+
+
 def random_shape_spec(seed):
     """A seeded odd-shaped layer: head counts, group sizes, head_dim, chunk lengths (one of them may be
     empty), prompt length and chunk order all drawn, to reach the ragged paths of every kernel."""
