@@ -861,14 +861,19 @@ bool attention_mfma_supported(const ifkv_ctx *ctx) {
 
 namespace {
 
-// How many parts the kv axis of the default kernel is cut into.  The chip holds 512 of these
-// workgroups at a time (two per CU).  When a launch has no more jobs than slots, the longest row
-// blocks alone set the finish time and cutting them pays (32K context, 5 % of the rows, 416 jobs:
-// 0.66 -> 0.52 ms with two parts; 8K context, 312 jobs: 0.150 -> 0.130 ms); with more jobs the
-// greedy dispatch already evens them out and the partial writes plus the combine pass cost more
-// than the split gains (684 jobs: 0.465 -> 0.496 ms; 1232 jobs: 1.28 -> 1.37 ms), so those
-// launches are not split.  A part spans at least 32 tiles.  IFKV_ATTN_SPLIT=<n> overrides
-// (tuning aid).
+// Whether and where the kv axis of the default kernel is cut.  The chip holds 512 of these workgroups
+// at a time (two per CU) and a row block at position p costs p keys, so a launch is bound either by
+// its total work (tiles per slot, if the jobs spread evenly) or by its longest row block alone.  With
+// rows spread uniformly over the context a job averages half the tiles of the cache; when the longest
+// job is clearly longer than the even share per slot, the kv axis is cut into parts of about that
+// share: row blocks shorter than one part are not affected (they write their output directly), only
+// the long ones run as several workgroups whose partial results are merged by the combine pass.
+// Measured at 32K context: 5 % of the rows (416 jobs) 0.66 -> 0.48 ms; 8K context (312 jobs) 0.150 ->
+// 0.125 ms.  Only launches with no more jobs than slots are cut: with more, every slot is busy for
+// most of the launch anyway and the partial writes plus the combine pass cost more than the shorter
+// tail gains (684 jobs: 0.469 -> 0.479 ms; 1232 jobs: 1.28 -> 1.37 ms).
+// A part spans at least 32 tiles.  IFKV_ATTN_SPLIT=<parts> (equal parts) and
+// IFKV_ATTN_PART_TILES=<tiles> override (tuning aids).
 struct SplitChoice {
   int parts, part_tiles;
 };
@@ -878,21 +883,24 @@ SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
   const int rpb = 128 / G;
   const int64_t jobs = ((n_rows + rpb - 1) / rpb) * d.n_kv_heads;
   const int n_kv_tiles = static_cast<int>((n_kv + TK - 1) / TK);
-  int parts = 1;
-  if (const char *env = getenv("IFKV_ATTN_SPLIT")) {
-    parts = atoi(env);
-  } else if (jobs > 0 && jobs <= 512) {
-    parts = 2;
-    while (parts < 8 && jobs * parts < 768) parts *= 2;  // about two jobs per slot
+  constexpr int kSlots = 512, kMinPartTiles = 32, kMaxParts = 8;
+  int part_tiles = n_kv_tiles;
+  if (const char *env = getenv("IFKV_ATTN_PART_TILES")) {
+    part_tiles = atoi(env);
+  } else if (const char *env2 = getenv("IFKV_ATTN_SPLIT")) {
+    const int parts = atoi(env2) > 0 ? atoi(env2) : 1;
+    part_tiles = (n_kv_tiles + parts - 1) / parts;
+  } else if (jobs > 0 && jobs <= kSlots) {
+    const double even_share = static_cast<double>(jobs) * (0.5 * n_kv_tiles) / kSlots;
+    if (even_share < 0.9 * n_kv_tiles) part_tiles = static_cast<int>(1.15 * even_share) + 1;
   }
-  const int max_parts = n_kv_tiles / 32 > 1 ? n_kv_tiles / 32 : 1;  // at least 32 tiles (2048 kv rows) per part
-  if (parts > max_parts) parts = max_parts;
-  if (parts > 8) parts = 8;
-  if (parts < 1) parts = 1;
+  if (part_tiles < kMinPartTiles) part_tiles = kMinPartTiles;
+  if (part_tiles * kMaxParts < n_kv_tiles) part_tiles = (n_kv_tiles + kMaxParts - 1) / kMaxParts;
+  if (part_tiles > n_kv_tiles) part_tiles = n_kv_tiles > 0 ? n_kv_tiles : 1;
   SplitChoice c;
-  c.part_tiles = (n_kv_tiles + parts - 1) / parts;
-  if (c.part_tiles < 1) c.part_tiles = 1;
-  c.parts = (n_kv_tiles + c.part_tiles - 1) / c.part_tiles;
+  c.part_tiles = part_tiles;
+  c.parts = (n_kv_tiles + part_tiles - 1) / part_tiles;
+  if (c.parts < 1) c.parts = 1;
   return c;
 }
 

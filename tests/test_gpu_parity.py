@@ -400,11 +400,12 @@ def attention_case_subsampled(spec, rows, n_check, flags=0):
     return to_host_f64(out, spec.dtype)[pick], lse.cpu().numpy().astype(np.float64)[pick], ref, lse_ref
 
 
-@pytest.mark.parametrize("parts", ["2", "3"])
-def test_attention_split_over_kv_axis(parts, monkeypatch):
+@pytest.mark.parametrize("var,value", [("IFKV_ATTN_SPLIT", "2"), ("IFKV_ATTN_SPLIT", "3"),
+                                       ("IFKV_ATTN_PART_TILES", "40")], ids=["2-parts", "3-parts", "40-tile-parts"])
+def test_attention_split_over_kv_axis(var, value, monkeypatch):
     """The default kernel with its kv axis cut into parts (partial results in scratch + combine pass),
     forced here; by itself the library splits only launches with few row blocks."""
-    monkeypatch.setenv("IFKV_ATTN_SPLIT", parts)
+    monkeypatch.setenv(var, value)   # 40-tile parts: row blocks of up to 40 tiles stay whole, longer ones get 2 or 3 parts
     spec = preset("C2", chunk_lens=[640] * 10, m_prompt=8)            # 100 kv tiles
     rows = np.unique(np.concatenate([sample_rows(6400, 900, 5), [0, 63, 64, 2111, 2112, 2113, 4223, 4224, 6399]]))
     out, lse, ref, lse_ref = attention_case_subsampled(spec, rows, 200)
