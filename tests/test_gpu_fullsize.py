@@ -139,3 +139,42 @@ def test_splice_and_attention_sampled_rows(run):
     # property at any size: outputs are convex combinations of V rows
     vmax = np.abs(V64).max()
     assert np.abs(to_host_f64(out, spec.dtype)).max() <= vmax * 1.01
+
+
+def test_attention_at_the_other_ratios(run):
+    """Stage 4 at the remaining recompute ratios of the configuration (at 5 % the launch is cut along
+    the kv axis and merged by the combine pass; at 30 % it is twice the benchmark's size); sampled rows
+    against the oracle, plus every row of the cut launch against the same rows computed uncut."""
+    spec, wl, N, L = run["spec"], run["wl"], run["N"], run["L"]
+    others = [r for r in spec.ratios if r != 0.15]
+    if run["name"] != "C3" or not others:
+        pytest.skip("one configuration carries several ratios")
+    s_gpu = run["s"].cpu().numpy()
+    K64 = V64 = None
+    for ratio in others:
+        idx = O.select_topk(s_gpu, O.budget(N, ratio))
+        q_sel, _, _ = make_recompute_inputs(wl, idx)
+        idx_d = torch.from_numpy(idx.astype(np.int32)).to(DEV)
+        qd = to_dev(q_sel, spec.dtype)
+        out, lse = L.recompute_attention(qd, idx_d, run["K"], run["V"], return_lse=True)
+        torch.cuda.synchronize()
+        if K64 is None:
+            K64, V64 = to_host_f64(run["K"], spec.dtype), to_host_f64(run["V"], spec.dtype)
+        pick = np.unique(np.concatenate([[0, 1, len(idx) - 2, len(idx) - 1], rng(11).choice(len(idx), 40, replace=False)]))
+        ref, lse_ref = O.recompute_attention(to_f64(q_sel, spec.dtype)[pick], idx[pick], K64, V64, wl.sm_scale)
+        assert np.abs(to_host_f64(out, spec.dtype)[pick] - ref).max() <= 2e-2
+        assert np.abs(lse.cpu().numpy().astype(np.float64)[pick] - lse_ref).max() <= 2e-2
+        # the same rows as part of a launch that is large enough not to be cut: identical arithmetic per
+        # row up to the order in which the parts are merged
+        big = O.select_topk(s_gpu, O.budget(N, 0.30))
+        if len(idx) < len(big):
+            pos = np.searchsorted(big, idx)
+            common = big[np.minimum(pos, len(big) - 1)] == idx
+            q_big, _, _ = make_recompute_inputs(wl, big)
+            q_big[pos[common]] = q_sel[common]
+            out_big = L.recompute_attention(to_dev(q_big, spec.dtype), torch.from_numpy(big.astype(np.int32)).to(DEV),
+                                            run["K"], run["V"])
+            torch.cuda.synchronize()
+            a = to_host_f64(out, spec.dtype)[common]
+            b = to_host_f64(out_big, spec.dtype)[pos[common]]
+            assert np.abs(a - b).max() <= 2e-2
