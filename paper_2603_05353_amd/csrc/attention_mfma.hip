@@ -919,23 +919,25 @@ size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t
   return align256(slots * D * sizeof(float)) + align256(slots * sizeof(float2)) + align256(n_rb * sizeof(int));
 }
 
-hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
-                                 const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
-                                 float *lse_out) {
+namespace {
+
+// One launch covers at most 65535 row blocks (the y extent of a grid); more rows than that are
+// served by several launches over consecutive row ranges (rows are independent).
+constexpr int64_t kMaxRowBlocks = 65535;
+
+hipError_t launch_attention_range(ifkv_ctx *ctx, const uint16_t *q_sel, const int32_t *row_pos, int64_t n_rows,
+                                  const uint16_t *k_cache, const uint16_t *v_cache, int64_t n_kv, uint16_t *out,
+                                  float *lse_out, bool wide) {
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
   const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
-  {
-    const char *env = getenv("IFKV_ATTN_WIDE");  // tuning aid: same as the layer flag
-    if ((d.flags & IFKV_FLAG_ATTN_WIDE) || (env != nullptr && atoi(env) == 1)) {
-      const int rpbw = 256 / G;
-      dim3 gridw(d.n_kv_heads, static_cast<unsigned>((n_rows + rpbw - 1) / rpbw));
-      hipLaunchKernelGGL(attn_wide_kernel, gridw, dim3(256), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
-                         row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
-                         static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
-                         lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpbw);
-      return hipGetLastError();
-    }
+  if (wide) {
+    const int rpbw = 256 / G;
+    dim3 gridw(d.n_kv_heads, static_cast<unsigned>((n_rows + rpbw - 1) / rpbw));
+    hipLaunchKernelGGL(attn_wide_kernel, gridw, dim3(256), 0, ctx->stream, q_sel, row_pos, static_cast<int>(n_rows),
+                       k_cache, v_cache, static_cast<int>(n_kv), out, lse_out, d.n_q_heads, d.n_kv_heads, scale_log2,
+                       rpbw);
+    return hipGetLastError();
   }
   const int rpb = 128 / G;
   const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
@@ -953,17 +955,42 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
     sp.block_tiles = reinterpret_cast<int *>(base + align256(slots * D * sizeof(float)) + align256(slots * sizeof(float2)));
   }
   dim3 grid(d.n_kv_heads, n_rb, sc.parts);
-  hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, static_cast<const uint16_t *>(q_sel),
-                     row_pos, static_cast<int>(n_rows), static_cast<const uint16_t *>(k_cache),
-                     static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), static_cast<uint16_t *>(out),
-                     lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb, sp);
+  hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, q_sel, row_pos, static_cast<int>(n_rows),
+                     k_cache, v_cache, static_cast<int>(n_kv), out, lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb,
+                     sp);
   if (sc.parts > 1) {
     const int64_t items = n_rows * d.n_q_heads;
     hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, ctx->stream, sp,
-                       row_pos, static_cast<int>(n_rows), static_cast<int>(n_kv), d.n_q_heads, rpb,
-                       static_cast<uint16_t *>(out), lse_out);
+                       row_pos, static_cast<int>(n_rows), static_cast<int>(n_kv), d.n_q_heads, rpb, out, lse_out);
   }
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
+                                 const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
+                                 float *lse_out) {
+  const auto &d = ctx->desc;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const char *env = getenv("IFKV_ATTN_WIDE");  // tuning aid: same as the layer flag
+  const bool wide = (d.flags & IFKV_FLAG_ATTN_WIDE) || (env != nullptr && atoi(env) == 1);
+  int64_t max_rb = kMaxRowBlocks;
+  if (const char *env_rb = getenv("IFKV_ATTN_MAX_ROW_BLOCKS")) {  // testing aid: exercise the range loop
+    const int64_t v = atoll(env_rb);
+    if (v >= 1 && v < max_rb) max_rb = v;
+  }
+  const int64_t rows_per_launch = max_rb * ((wide ? 256 : 128) / G);
+  const int64_t row_elems = static_cast<int64_t>(d.n_q_heads) * D;
+  for (int64_t r0 = 0; r0 < n_rows; r0 += rows_per_launch) {
+    const int64_t nr = n_rows - r0 < rows_per_launch ? n_rows - r0 : rows_per_launch;
+    hipError_t e = launch_attention_range(ctx, static_cast<const uint16_t *>(q_sel) + r0 * row_elems, row_pos + r0, nr,
+                                          static_cast<const uint16_t *>(k_cache), static_cast<const uint16_t *>(v_cache),
+                                          n_kv, static_cast<uint16_t *>(out) + r0 * row_elems,
+                                          lse_out != nullptr ? lse_out + r0 * d.n_q_heads : nullptr, wide);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace ifkv

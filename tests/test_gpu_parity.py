@@ -414,6 +414,18 @@ def test_attention_split_over_kv_axis(var, value, monkeypatch):
 
 
 @pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
+def test_attention_in_several_row_ranges(flags, monkeypatch):
+    """More row blocks than one grid holds are served by several launches over consecutive row ranges;
+    the limit is lowered here so that a small case takes that path (7 launches of 3 row blocks)."""
+    monkeypatch.setenv("IFKV_ATTN_MAX_ROW_BLOCKS", "3")
+    spec = preset("C2", chunk_lens=[300, 340], m_prompt=8)
+    rows = sample_rows(640, 600 if flags == 0 else 640, 9)
+    out, lse, ref, lse_ref = attention_case(spec, rows, flags=flags)
+    assert np.abs(out - ref).max() <= 2e-2
+    assert np.abs(lse - lse_ref).max() <= 2e-2
+
+
+@pytest.mark.parametrize("flags", [0, ATTN_WIDE], ids=["default", "wide"])
 def test_attention_full_ratio_is_dense_causal(flags):
     spec = preset("C2", chunk_lens=[150, 83], m_prompt=8)
     out, lse, ref, lse_ref = attention_case(spec, np.arange(233), flags=flags)
