@@ -55,6 +55,8 @@ def parse():
     ap.add_argument("--zero-inputs", action="store_true",
                     help="profiling aid for --only recompute_attention: all-zero K, V and queries (same instruction "
                          "stream, least switching activity: shows how far the clock drops on real data)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="launch-shape knob of include/ifkv_debug.h (sweeps), e.g. attn_wg_per_head=48")
     ap.add_argument("--only", default=None,
                     choices=["reposition_keys", "score_tokens", "select_topk", "splice_kv",
                              "recompute_attention", "copy"],
@@ -96,6 +98,9 @@ def main():
 
     L = pkg.Layer(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.rope_theta,
                   max_ctx=N, max_prompt=M)
+    for kv in args.tune:
+        key, value = kv.split("=")
+        L.set_tuning(key, int(value))
     kd = [dev_t(c) for c in wl.k_chunks]
     vd = [dev_t(c) for c in wl.v_chunks]
     qd = dev_t(wl.q_prompt)

@@ -25,8 +25,10 @@
  *   call is made; "host" pointers are ordinary host memory, read before the
  *   call returns.  The caller owns every buffer passed in; the library never
  *   frees, reallocates or keeps a caller pointer after the call's kernels end.
- *   The context owns only its own scratch memory (allocated lazily on the
- *   first call that needs it, freed by ifkv_destroy).
+ *   The context owns only its own scratch memory: one allocation, sized from
+ *   the layer descriptor (max_ctx, max_prompt, head counts), made by the first
+ *   stage call that needs scratch and freed by ifkv_destroy.  No later call
+ *   allocates, frees or synchronises.
  * - All device work is enqueued on the context's HIP stream and the calls
  *   return without waiting for it.  Host outputs (chunk starts, N, k) are
  *   computed on the host from host inputs and are valid on return.
@@ -62,20 +64,14 @@ typedef enum {
 
 typedef enum { IFKV_F32 = 0, IFKV_BF16 = 1 } ifkv_dtype;
 
-/* Which coordinates form a rotary 2-D pair (Preliminary, "Rotary Positional
- * Embedding": "vectors decomposed into 2D subspaces").  HALF couples
- * (x_i, x_{i+d/2}); INTERLEAVED couples (x_{2i}, x_{2i+1}). */
+/* Which two coordinates are rotated together as one plane (Preliminary, "Rotary
+ * Positional Embedding", Eq. (3)).  HALF couples (x_i, x_{i+d/2}); INTERLEAVED
+ * couples (x_{2i}, x_{2i+1}). */
 typedef enum { IFKV_ROPE_HALF = 0, IFKV_ROPE_INTERLEAVED = 1 } ifkv_rope_pairing;
 
 /* Route every stage through the plain fp32 ALU kernels even where a bf16 MFMA
  * kernel exists (cross-checking and debugging). */
 #define IFKV_FLAG_FORCE_GENERIC 1u
-/* Stage 4, bf16, head_dim 128: use the one-wavefront-per-SIMD kernel (64 query
- * columns per wavefront, software-pipelined over half tiles) instead of the
- * default two-wavefront kernel.  Same results to the stage's tolerance; an
- * alternative schedule kept for tuning, not the faster one at the measured
- * shapes. */
-#define IFKV_FLAG_ATTN_WIDE 2u
 
 typedef struct {
   int32_t dtype;      /* ifkv_dtype of K, V, Q and attention outputs */
@@ -242,9 +238,9 @@ int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new,
 
 /*
  * Glue between the model's projections and stages 4/5 -- "KV Recomputation":
- * a selected token runs a standard forward pass "placed at its global
- * position", so its freshly projected query and key rows carry the rotary
- * embedding of Eq. (3)-(4) at that position.  Row r of x is turned, in every
+ * the forward pass of a selected token runs at the token's position in the
+ * concatenated sequence, so its freshly projected query and key rows carry the
+ * rotary embedding of Eq. (3)-(4) at that position.  Row r of x is turned, in every
  * 2-D pair j, by pos[r] * theta_j; angles are formed in fp64, the rotation runs
  * in fp32 and is rounded once to the storage dtype.  In place.  (The
  * projections themselves need the model's weights and are not part of this
@@ -295,33 +291,6 @@ int ifkv_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, int32_t n_sl
  */
 int ifkv_reorder_chunks(ifkv_ctx *ctx, int32_t n_chunks, const int32_t *order_in, const int32_t *slot_counts,
                         const int32_t *chunk_len, int32_t *order_out);
-
-/*
- * Calibration utility (not part of the method): a plain streaming copy of
- * n_bytes (multiple of 16, both pointers 16-byte aligned, device memory) with
- * the same load/store shape the streaming stages use.  The benchmark times it
- * to state the HBM bandwidth the machine actually delivers next to the
- * published peak, and hardware-counter readings are scaled by what the same
- * counters read for this kernel.
- */
-int ifkv_copy_bytes(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes);
-
-/*
- * Calibration utility (not part of the method): a loop of independent
- * 32x32x16 bf16 MFMAs on register-resident operands, two wavefronts per SIMD on
- * every compute unit.  The benchmark times it to state what the matrix pipes
- * sustain on this machine next to the published peak.
- *   pattern     0: every operand element is 1.0 (least switching activity);
- *               1: pseudo-random sign and mantissa, magnitudes in [0.5, 2)
- *   iterations  loop trips per wavefront, 1 .. 10^7 (32 MFMAs per trip)
- *   sink        device, at least ifkv_mfma_probe_sink_floats() floats; receives
- *               one checksum per thread (content is not meaningful)
- *   flops_out   host, nullable: floating-point operations one launch performs
- * Errors: IFKV_EINVAL for a NULL ctx or sink, an unknown pattern or an
- * iteration count out of range.
- */
-int ifkv_mfma_probe(ifkv_ctx *ctx, int pattern, int64_t iterations, float *sink, double *flops_out);
-int64_t ifkv_mfma_probe_sink_floats(void);
 
 #ifdef __cplusplus
 }

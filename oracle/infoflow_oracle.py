@@ -232,10 +232,10 @@ def splice_kv(k_cache: np.ndarray, v_cache: np.ndarray, k_new: np.ndarray,
 # ---------------------------------------------------------------------------
 def rope_rows(x: np.ndarray, pos: np.ndarray, theta: float, pairing: str = "half",
               freqs: Optional[np.ndarray] = None) -> np.ndarray:
-    """"KV Recomputation": a selected token runs a standard forward pass "placed
-    at its global position", so its freshly projected query and key rows get the
-    rotary embedding of Eq. (3)-(4) at that position: row r, pair j is turned by
-    pos[r] * theta_j.  x [R, H, d]; pos [R] (integers)."""
+    """"KV Recomputation": the forward pass of a selected token runs at the
+    token's position in the concatenated sequence, so its freshly projected
+    query and key rows get the rotary embedding of Eq. (3)-(4) at that position:
+    row r, pair j is turned by pos[r] * theta_j.  x [R, H, d]; pos [R] (integers)."""
     d = x.shape[-1]
     th = rope_frequencies(d, theta) if freqs is None else np.asarray(freqs, dtype=np.float64)
     out = np.empty_like(np.asarray(x, dtype=np.float64))

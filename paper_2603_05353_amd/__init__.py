@@ -1,7 +1,6 @@
 """MI355X-native selective-recompute path of InfoFlow KV (HIP kernels behind a
 C ABI, see include/ifkv.h).  The shared library is loaded on first use."""
 from .binding import (  # noqa: F401
-    IFKV_FLAG_ATTN_WIDE,
     IFKV_FLAG_FORCE_GENERIC,
     IfkvError,
     Layer,

@@ -21,13 +21,13 @@ IFKV_OK, IFKV_EINVAL, IFKV_ESHAPE, IFKV_EDTYPE, IFKV_ENOMEM, IFKV_EHIP = 0, -1, 
 IFKV_F32, IFKV_BF16 = 0, 1
 IFKV_ROPE_HALF, IFKV_ROPE_INTERLEAVED = 0, 1
 IFKV_FLAG_FORCE_GENERIC = 1
-IFKV_FLAG_ATTN_WIDE = 2
 
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
     "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
     "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
-    "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",
+    "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",   # include/ifkv_calibrate.h
+    "ifkv_set_tuning",                                                       # include/ifkv_debug.h
 )
 
 
@@ -92,6 +92,8 @@ def load_library() -> C.CDLL:
     lib.ifkv_mfma_probe.restype = C.c_int
     lib.ifkv_mfma_probe_sink_floats.argtypes = []
     lib.ifkv_mfma_probe_sink_floats.restype = i64
+    lib.ifkv_set_tuning.argtypes = [vp, C.c_char_p, i64]
+    lib.ifkv_set_tuning.restype = C.c_int
     _lib = lib
     return lib
 
@@ -248,6 +250,10 @@ class Layer:
         self._check(self._lib.ifkv_reorder_chunks(self._ctx, n, _i32_array(order_in), _i32_array(slot_counts),
                                                   _i32_array(chunk_len), out))
         return [int(out[i]) for i in range(n)]
+
+    def set_tuning(self, key: str, value: int) -> None:
+        """Tuning / testing knob of include/ifkv_debug.h (host only)."""
+        self._check(self._lib.ifkv_set_tuning(self._ctx, key.encode(), int(value)))
 
     def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor) -> None:
         self._check(self._lib.ifkv_copy_bytes(self._ctx, _ptr(dst), _ptr(src), src.numel() * src.element_size()))

@@ -133,9 +133,9 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos,
 
 }  // namespace
 
-size_t attention_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
+size_t attention_scratch_bytes(const ifkv_ctx *ctx) {
   const bool generic = (ctx->desc.flags & IFKV_FLAG_FORCE_GENERIC) || !attention_mfma_supported(ctx);
-  return generic ? 0 : attention_mfma_scratch_bytes(ctx, n_rows, n_kv);
+  return generic ? 0 : attention_mfma_scratch_bytes(ctx);
 }
 
 hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,

@@ -6,8 +6,11 @@
 namespace ifkv {
 
 bool attention_mfma_supported(const ifkv_ctx *ctx);
-// Scratch the MFMA path needs for the partial results of a launch split over the kv axis (0 if not split).
-size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv);
+// Scratch the MFMA path needs for the partial results of row blocks cut between workgroups: fixed
+// for a layer shape.
+size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx);
+// Host-side bounds check of one launch against the allocated scratch and the plan's capacity.
+bool attention_mfma_launch_fits(const ifkv_ctx *ctx, int wg_per_head, int64_t n_row_blocks);
 hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                                  const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                                  float *lse_out);

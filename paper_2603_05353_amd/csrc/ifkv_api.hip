@@ -9,6 +9,8 @@
 #include <new>
 #include <vector>
 
+#include "ifkv_calibrate.h"
+#include "ifkv_debug.h"
 #include "ifkv_internal.h"
 
 namespace {
@@ -32,16 +34,15 @@ int hip_fail(ifkv_ctx *ctx, hipError_t e, const char *what) {
   return fail(ctx, IFKV_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Grows the context's scratch buffer to at least `bytes`.
-int ensure_scratch(ifkv_ctx *ctx, size_t bytes) {
-  if (bytes <= ctx->scratch_bytes) return IFKV_OK;
-  if (ctx->scratch != nullptr) {
-    hipError_t e = hipStreamSynchronize(ctx->stream);  // earlier kernels may still use the old buffer
-    if (e != hipSuccess) return hip_fail(ctx, e, "hipStreamSynchronize");
-    (void)hipFree(ctx->scratch);
-    ctx->scratch = nullptr;
-    ctx->scratch_bytes = 0;
-  }
+// The context's scratch: ONE allocation, on the first stage call that needs scratch, sized for the
+// largest request any stage can make under the layer descriptor (the stages run one after the other
+// on one stream and share it).  No later call allocates, frees or synchronises.
+int ensure_scratch(ifkv_ctx *ctx) {
+  if (ctx->scratch != nullptr) return IFKV_OK;
+  size_t bytes = ifkv::score_scratch_bytes(ctx, ctx->desc.max_ctx, ctx->desc.max_prompt);
+  bytes = std::max(bytes, ifkv::topk_scratch_bytes(ctx, ctx->desc.max_ctx));
+  bytes = std::max(bytes, ifkv::attention_scratch_bytes(ctx));
+  bytes = std::max<size_t>(bytes, 256);
   void *p = nullptr;
   hipError_t e = hipMalloc(&p, bytes);
   if (e != hipSuccess) {
@@ -223,7 +224,7 @@ int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const 
     return fail(ctx, IFKV_EINVAL, "score_tokens: k_global and q_prompt are required");
   if (!aligned16(k_global) || !aligned16(q_prompt) || !aligned16(k_prompt))
     return fail(ctx, IFKV_EINVAL, "score_tokens: inputs must be 16-byte aligned");
-  int rc = ensure_scratch(ctx, ifkv::score_scratch_bytes(ctx, n_ctx, m_prompt));
+  int rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
   hipError_t e = ifkv::launch_score(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate != 0, scores);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "score kernel launch");
@@ -249,7 +250,7 @@ int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double r
   if (k_out != nullptr) *k_out = k;
   if (k == 0) return IFKV_OK;
   if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk: NULL pointer");
-  int rc = ensure_scratch(ctx, ifkv::topk_scratch_bytes(ctx, n_ctx));
+  int rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
   hipError_t e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "top-k kernel launch");
@@ -270,7 +271,7 @@ int ifkv_recompute_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *ro
     return fail(ctx, IFKV_EINVAL, "recompute_attention: NULL pointer");
   if (!aligned16(q_sel) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
     return fail(ctx, IFKV_EINVAL, "recompute_attention: tensors must be 16-byte aligned");
-  int rc = ensure_scratch(ctx, ifkv::attention_scratch_bytes(ctx, n_rows, n_kv));
+  int rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
   hipError_t e = ifkv::launch_attention(ctx, q_sel, row_pos, n_rows, k_cache, v_cache, n_kv, out, lse_out);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "attention kernel launch");
@@ -361,6 +362,28 @@ int ifkv_reorder_chunks(ifkv_ctx *ctx, int32_t n_chunks, const int32_t *order_in
   });
   for (int32_t s = 0; s < n_chunks; ++s) order_out[s] = order[slot[s]];
   return IFKV_OK;
+}
+
+int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (key == nullptr) return fail(ctx, IFKV_EINVAL, "set_tuning: key is NULL");
+  const int64_t wg_max = std::max(1, 512 / ctx->desc.n_kv_heads);
+  struct Knob {
+    const char *name;
+    int *slot;
+    int64_t hi;
+  } knobs[] = {{"attn_wg_per_head", &ctx->tune.attn_wg_per_head, wg_max},
+               {"attn_min_share_tiles", &ctx->tune.attn_min_share_tiles, 1 << 20},
+               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 3072}};
+  for (const Knob &k : knobs) {
+    if (std::strcmp(key, k.name) != 0) continue;
+    if (value < 0 || value > k.hi)
+      return fail(ctx, IFKV_EINVAL, "set_tuning: %s=%lld is outside [0, %lld]", key, static_cast<long long>(value),
+                  static_cast<long long>(k.hi));
+    *k.slot = static_cast<int>(value);
+    return IFKV_OK;
+  }
+  return fail(ctx, IFKV_EINVAL, "set_tuning: unknown key '%s'", key);
 }
 
 int ifkv_copy_bytes(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes) {

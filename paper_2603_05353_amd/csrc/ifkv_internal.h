@@ -9,8 +9,16 @@
 
 #include "ifkv.h"
 
+// Tuning and testing knobs (include/ifkv_debug.h); 0 = the library's own choice.
+struct ifkv_tuning {
+  int attn_wg_per_head = 0;      // stage 4: workgroups per kv head (can only lower the default)
+  int attn_min_share_tiles = 0;  // stage 4: smallest share of kv tiles worth a workgroup
+  int attn_max_row_blocks = 0;   // stage 4: row blocks per launch (can only lower the default)
+};
+
 struct ifkv_ctx {
   ifkv_layer_desc desc;
+  ifkv_tuning tune;
   hipStream_t stream = nullptr;
   float sm_scale = 0.f;
   double inv_freq[128];         // d/2 entries, host copy
@@ -57,7 +65,7 @@ size_t topk_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx);
 hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out);
 
 // Stage 4.
-size_t attention_scratch_bytes(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv);
+size_t attention_scratch_bytes(const ifkv_ctx *ctx);
 hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                             float *lse_out);

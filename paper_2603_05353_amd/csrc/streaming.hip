@@ -229,9 +229,9 @@ __global__ __launch_bounds__(kThreads) void splice_kernel(const v4u *__restrict_
 }
 
 // ---------------------------------------------------------------------------
-// Rotary embedding of recomputed rows -- "KV Recomputation": a selected token is "placed at its
-// global position", so its freshly projected query/key row r is turned by pos[r] * theta_j in
-// every pair j (Eq. 3-4).  One workgroup per row; the first d/2 threads form the row's cos/sin
+// Rotary embedding of recomputed rows -- "KV Recomputation": the forward pass of a selected token
+// runs at the token's position in the concatenated sequence, so its freshly projected query/key
+// row r is turned by pos[r] * theta_j in every pair j (Eq. 3-4).  One workgroup per row; the first d/2 threads form the row's cos/sin
 // in fp64 (positions reach 1e5: an fp32 angle would be off by 1e-2 rad), the rotation itself is
 // fp32 FMA, rounded once to the storage type.  In place.
 // ---------------------------------------------------------------------------

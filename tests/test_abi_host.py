@@ -12,10 +12,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def header_symbols():
-    with open(os.path.join(ROOT, "include", "ifkv.h")) as f:
-        text = f.read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ifkv_[a-z_]+)\s*\(", text)))
+    """Every function declared in include/*.h (the method's ABI, the calibration kernels, the tuning aids)."""
+    syms = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        with open(os.path.join(inc, fn)) as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        syms |= set(re.findall(r"\b(ifkv_[a-z_]+)\s*\(", text))
+    return sorted(syms)
 
 
 @pytest.fixture(scope="module")
@@ -198,4 +205,21 @@ def test_mfma_probe_rejects_bad_arguments(lib):
     assert lib.ifkv_mfma_probe(L._ctx, 1, 10, None, C.byref(flops)) == B.IFKV_EINVAL
     assert lib.ifkv_mfma_probe(None, 1, 10, fake, C.byref(flops)) == B.IFKV_EINVAL
     assert flops.value == -1.0
+    L.close()
+
+
+def test_set_tuning_validation(lib):
+    L = _layer()
+    L.set_tuning("attn_wg_per_head", 3)
+    L.set_tuning("attn_wg_per_head", 64)          # 512 / 8 kv heads: the default is the upper limit
+    L.set_tuning("attn_max_row_blocks", 2)
+    L.set_tuning("attn_min_share_tiles", 1)
+    L.set_tuning("attn_min_share_tiles", 0)
+    for key, value in [("attn_wg_per_head", 65), ("attn_wg_per_head", -1), ("attn_max_row_blocks", 3073),
+                       ("no_such_knob", 1)]:
+        with pytest.raises(B.IfkvError) as e:
+            L.set_tuning(key, value)
+        assert e.value.code == B.IFKV_EINVAL
+    assert lib.ifkv_set_tuning(L._ctx, None, 1) == B.IFKV_EINVAL
+    assert lib.ifkv_set_tuning(None, b"attn_wg_per_head", 1) == B.IFKV_EINVAL
     L.close()

@@ -508,3 +508,55 @@ def test_rope_rows_against_complex_multiplication_and_composition():
         n0 = np.hypot(x[..., :4], x[..., 4:]) if pairing == "half" else np.hypot(x[..., 0::2], x[..., 1::2])
         n1 = np.hypot(got[..., :4], got[..., 4:]) if pairing == "half" else np.hypot(got[..., 0::2], got[..., 1::2])
         assert np.allclose(n0, n1, rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# caller-supplied frequency table (Eq. 4 replaced by an explicit table, e.g. a
+# frequency-rescaled one for long-context checkpoints)
+# --------------------------------------------------------------------------
+def _custom_freqs(half):
+    """A table that is neither geometric nor monotone, so that a transposed,
+    reversed, truncated or ignored table cannot reproduce it."""
+    return np.array([0.37 / (1 + j) + (0.011 if j % 3 == 0 else 0.0) + 0.002 * ((7 * j) % 5) for j in range(half)])
+
+
+@pytest.mark.parametrize("pairing", ["half", "interleaved"])
+def test_custom_frequency_table_is_used_pair_by_pair(pairing):
+    g = rng(61)
+    d, H = 16, 2
+    freqs = _custom_freqs(d // 2)
+    lens = [3, 4, 2]
+    order = [2, 0, 1]
+    pos0 = [0, 5, 1]
+    chunks = [g.standard_normal((L, H, d)) for L in lens]
+    K, _, start, N = O.reposition_keys(chunks, None, lens, order, theta=123.0, pairing=pairing,
+                                       cached_pos0=pos0, freqs=freqs)
+    assert start.tolist() == [2, 5, 0] and N == 9      # slots: chunk 2 (2 rows), chunk 0 (3), chunk 1 (4)
+    for c, L in enumerate(lens):
+        adv = int(start[c]) - pos0[c]
+        for p in range(L):
+            for h in range(H):
+                for j in range(d // 2):
+                    ia, ib = (j, j + d // 2) if pairing == "half" else (2 * j, 2 * j + 1)
+                    z = complex(chunks[c][p, h, ia], chunks[c][p, h, ib]) * cmath.exp(1j * adv * freqs[j])
+                    assert abs(K[start[c] + p, h, ia] - z.real) < 1e-12
+                    assert abs(K[start[c] + p, h, ib] - z.imag) < 1e-12
+    # the table replaces the base entirely: a different base gives the same result,
+    # and leaving the table out (same base) gives a different one
+    K2, _, _, _ = O.reposition_keys(chunks, None, lens, order, theta=5e5, pairing=pairing, cached_pos0=pos0, freqs=freqs)
+    assert np.array_equal(K, K2)
+    K3, _, _, _ = O.reposition_keys(chunks, None, lens, order, theta=123.0, pairing=pairing, cached_pos0=pos0)
+    assert np.abs(K - K3).max() > 0.1
+    # rows at given positions: the same table, pair by pair
+    x = g.standard_normal((5, H, d))
+    pos = np.array([0, 1, 9, 1000, 131071])
+    y = O.rope_rows(x, pos, 123.0, pairing, freqs=freqs)
+    for r in range(5):
+        for h in range(H):
+            for j in range(d // 2):
+                ia, ib = (j, j + d // 2) if pairing == "half" else (2 * j, 2 * j + 1)
+                z = complex(x[r, h, ia], x[r, h, ib]) * cmath.exp(1j * int(pos[r]) * freqs[j])
+                assert abs(y[r, h, ia] - z.real) < 1e-9 and abs(y[r, h, ib] - z.imag) < 1e-9
+    # geometric table passed explicitly == the default built from the base
+    geo = np.array([123.0 ** (-2.0 * j / d) for j in range(d // 2)])
+    assert np.array_equal(O.rope_rows(x, pos, 123.0, pairing, freqs=geo), O.rope_rows(x, pos, 123.0, pairing))
