@@ -28,19 +28,18 @@
 // Work distribution.  A row block at position p costs p/64 + 1 tiles, so the blocks of one launch
 // differ in length by two orders of magnitude while the chip holds only 512 of these workgroups at
 // a time (two per CU): handing out whole row blocks leaves an eighth of the machine idle at the
-// end of a launch.  Instead the launch has a fixed number of workgroups per kv head, and the
-// (row block, kv tile) pairs of a head -- row blocks in descending length, tiles ascending -- form
-// one line of T tiles that is cut into equal contiguous shares, one per workgroup.  A share covers
-// the end of one row block, some whole row blocks and the beginning of another; whole row blocks
-// are written to the output directly, and the at most two cut ones per workgroup leave their
-// unnormalised O, reference max and sum in scratch, merged by attn_combine_kernel (run by the
-// workgroup slot whose share holds the row block's last tile).  Every workgroup derives the plan
-// by itself from row_pos (a prefix sum over the row blocks' tile counts in LDS): no extra launch,
-// no host knowledge of the positions.
-#include "attention_common.h"
-#include "ifkv_device.h"
+// end of a launch, and cutting the blocks' tiles into equal contiguous shares makes every workgroup
+// stream its own stretch of K/V through the fabric (6.8 GB per launch instead of 0.8 GB measured at
+// 32K context).  The launch therefore has a fixed number of workgroups per kv head that walk the
+// (kv range, row block, tile) line of attention_plan.h in step: at any time they read the same few
+// K/V tiles, and all end together.  Pieces that are not a whole row block leave their unnormalised
+// O, reference max and sum in a scratch slot and count their tiles on the row block; the workgroup
+// that completes the count merges the pieces.  Every workgroup derives the plan by itself from
+// row_pos: no extra launch, no host knowledge of the positions, and nobody waits for anybody.
+#include <algorithm>
 
 #include "attention_common.h"
+#include "attention_plan.h"
 #include "ifkv_device.h"
 
 namespace ifkv {
@@ -391,104 +390,230 @@ __device__ __forceinline__ void store_output(const f32x16 (&O)[4], float m_ref, 
 }
 
 // ---------------------------------------------------------------------------
-// The plan: which (row block, tile range) pairs a workgroup processes.
+// The plan (attention_plan.h) built in LDS by every workgroup for itself: no extra launch, no host
+// knowledge of the positions.
 // ---------------------------------------------------------------------------
-constexpr int kPlanMaxBlocks = 3072;   // row blocks one launch can plan (prefix sums live in LDS, 12 KiB)
 constexpr int kThreads = 256;
 
 struct PlanArgs {
   int n_rb;             // row blocks of this launch (<= kPlanMaxBlocks)
   int wg_per_head;      // workgroups per kv head
-  int min_share;        // smallest share worth a workgroup, in tiles
-  float *o_part;        // [2 * gridDim.x] x [NWAVES * 16 * 64] float4: unnormalised O in accumulator order
-  float2 *ml_part;      // [2 * gridDim.x] x [128]: (reference max in the log2 domain, sum) per query column
+  int tail_div;         // the short units at the end of the line are 1/tail_div of a kv range
+  int r_min;            // smallest kv range, in tiles (a power of two)
+  int slot_cap;         // partial slots per kv head
+  float *o_part;        // [n_kv_heads * slot_cap] x [128 * 128]: unnormalised O, see write_partial
+  float *ml_part;       // [n_kv_heads * slot_cap] x [128] x 2: (reference max in the log2 domain, sum) per query column
+  int *arrived;         // [n_kv_heads][kPlanMaxBlocks + 2]: tiles of a shared row block that are done, then the
+                        // units handed out beyond the first W and the workgroups that have left; zero between launches
+  unsigned long long *trace;  // tuning aid, normally null: [grid][kTraceWords] time stamps of thread 0 (100 MHz counter)
 };
+constexpr int kTraceWords = 64;
 constexpr size_t kPartFloats = 128 * D;  // O floats per partial slot
 
-// s_prefix[q] = tiles of the q longest row blocks, q = 0..n_rb; row block rb = n_rb-1-q (rows ascend,
-// so the last row block is the longest).  A row block's length is that of its last row, positions
-// clamped into the cache (rows outside it produce zeros and never extend a block).
-// Every thread of the workgroup must call this; ends with a barrier.
-__device__ __forceinline__ void build_prefix(int *s_prefix, int *s_wave, const int32_t *__restrict__ row_pos, int n_rows,
-                                             int n_kv, int n_rb, int rows_per_block) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int per = (n_rb + kThreads - 1) / kThreads;  // consecutive entries per thread
-  const int q0 = tid * per;
-  int sum = 0;
-  for (int i = 0; i < per; ++i) {
-    const int q = q0 + i;
-    if (q < n_rb) {
-      const int rb = n_rb - 1 - q;
-      const int last = min((rb + 1) * rows_per_block, n_rows) - 1;
-      const int p = min(max(row_pos[last], 0), n_kv - 1);
-      sum += p / TK + 1;
-    }
-  }
-  // exclusive scan of the per-thread sums over the workgroup
-  int incl = sum;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int v = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += v;
-  }
-  if (lane == 63) s_wave[wave] = incl;
-  __syncthreads();
-  int base = incl - sum;
-  for (int w = 0; w < wave; ++w) base += s_wave[w];
-  // second walk: the loads hit the cache this time
-  for (int i = 0; i < per; ++i) {
-    const int q = q0 + i;
-    if (q < n_rb) {
-      s_prefix[q] = base;
-      const int rb = n_rb - 1 - q;
-      const int last = min((rb + 1) * rows_per_block, n_rows) - 1;
-      const int p = min(max(row_pos[last], 0), n_kv - 1);
-      base += p / TK + 1;
-      if (q == n_rb - 1) s_prefix[n_rb] = base;
-    }
-  }
-  __syncthreads();
-}
-
-// Equal shares of the T tiles of one head over the workgroups that take part.
-struct Shares {
-  int total;   // T
-  int w_eff;   // workgroups with a non-empty share
-  __device__ __forceinline__ Shares(int total_tiles, int wg_per_head, int min_share) {
-    total = total_tiles;
-    w_eff = max(1, min(wg_per_head, total_tiles / max(min_share, 1)));
-  }
-  __device__ __forceinline__ int lo(int w) const {
-    return static_cast<int>((static_cast<int64_t>(w) * total) / w_eff);
-  }
-  // the workgroup whose share contains flat tile x
-  __device__ __forceinline__ int owner(int x) const {
-    return static_cast<int>(((static_cast<int64_t>(x) + 1) * w_eff - 1) / total);
-  }
+struct PlanTables {
+  int prefix[kPlanMaxBlocks + 1];
+  int r_base[kPlanMaxRanges + 1];
+  int r_full[kPlanMaxRanges];
+  int r_cnt[kPlanMaxRanges];
+  int r_part[kPlanMaxRanges + 1];
+  int wave_tmp[kThreads / 64][kPlanRangeChoices + 1];
 };
 
-// largest q in [0, n_rb) with s_prefix[q] <= x   (x < s_prefix[n_rb])
-__device__ __forceinline__ int block_of(const int *s_prefix, int n_rb, int x) {
-  int a = 0, b = n_rb;  // invariant: s_prefix[a] <= x < s_prefix[b]
-  while (b - a > 1) {
+// Exclusive prefix of one value per thread over the workgroup (thread order); *total gets the sum.
+// Every thread must call; ends with a barrier, so the scratch row can be reused right away.
+__device__ __forceinline__ int block_exclusive_scan(int v, int (*wave_tmp)[kPlanRangeChoices + 1], int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int u = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += u;
+  }
+  if (lane == 63) wave_tmp[wave][kPlanRangeChoices] = incl;
+  __syncthreads();
+  int base = incl - v, sum = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) {
+    const int x = wave_tmp[w][kPlanRangeChoices];
+    if (w < wave) base += x;
+    sum += x;
+  }
+  *total = sum;
+  __syncthreads();
+  return base;
+}
+
+// tiles of row block q (descending length order): that of its last row, positions clamped into the
+// cache (rows outside it produce zeros and never extend a block)
+__device__ __forceinline__ int block_tiles_of(const int32_t *__restrict__ row_pos, int n_rows, int n_kv, int n_rb,
+                                              int rows_per_block, int q) {
+  const int rb = n_rb - 1 - q;
+  const int last = min((rb + 1) * rows_per_block, n_rows) - 1;
+  return min(max(row_pos[last], 0), n_kv - 1) / TK + 1;
+}
+
+// number of row blocks with more than x tiles (tile counts do not increase with q)
+__device__ __forceinline__ int count_longer(const int *prefix, int n_rb, int x) {
+  int a = 0, b = n_rb;  // blocks [0, a) are longer, blocks [b, n_rb) are not
+  while (a < b) {
     const int mid = (a + b) >> 1;
-    if (s_prefix[mid] <= x) a = mid; else b = mid;
+    if (prefix[mid + 1] - prefix[mid] > x) a = mid + 1; else b = mid;
   }
   return a;
 }
 
-// Partial result of a cut row block, in the accumulator's own register order: every store
-// instruction of a wavefront writes 1 KiB of consecutive addresses.
-__device__ __forceinline__ void write_partial(const WaveState &w, float *o_slot, float2 *ml_slot, int hf) {
+// Every thread of the workgroup must call this.  Returns false (for every thread) if the launch
+// does not fit the slots, which the host rules out before launching.
+__device__ __forceinline__ bool build_plan(AttnPlan &p, PlanTables &t, const int32_t *__restrict__ row_pos, int n_rows,
+                                           int n_kv, int rows_per_block, const PlanArgs &pa) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_rb = pa.n_rb;
+  const int lg_min = 31 - __clz(pa.r_min);
+  // tiles per row block: prefix sums, and the number of parts for every candidate range length
+  const int per = (n_rb + kThreads - 1) / kThreads;
+  const int q0 = tid * per;
+  int sum = 0;
+  int parts[kPlanRangeChoices];
+#pragma unroll
+  for (int j = 0; j < kPlanRangeChoices; ++j) parts[j] = 0;
+  for (int i = 0; i < per; ++i) {
+    const int q = q0 + i;
+    if (q < n_rb) {
+      const int n = block_tiles_of(row_pos, n_rows, n_kv, n_rb, rows_per_block, q);
+      sum += n;
+#pragma unroll
+      for (int j = 0; j < kPlanRangeChoices; ++j) parts[j] += (n + (pa.r_min << j) - 1) >> (lg_min + j);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kPlanRangeChoices; ++j) {
+    const int s = wave_sum_i(parts[j]);
+    if (lane == 0) t.wave_tmp[wave][j] = s;
+  }
+  int total;
+  int base = block_exclusive_scan(sum, t.wave_tmp, &total);  // its first barrier also publishes the part counts
+  for (int i = 0; i < per; ++i) {  // second walk: the loads hit the cache this time
+    const int q = q0 + i;
+    if (q < n_rb) {
+      t.prefix[q] = base;
+      base += block_tiles_of(row_pos, n_rows, n_kv, n_rb, rows_per_block, q);
+    }
+  }
+  if (tid == 0) t.prefix[n_rb] = total;
+#pragma unroll
+  for (int j = 0; j < kPlanRangeChoices; ++j) {
+    int s = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) s += t.wave_tmp[w][j];
+    parts[j] = s;
+  }
+  __syncthreads();
+  const int n0 = t.prefix[1];
+  const int j = plan_choose_range(parts, n0, total, pa.r_min, pa.wg_per_head, pa.tail_div, pa.slot_cap);
+  if (j < 0) return false;
+  p.prefix = t.prefix;
+  p.r_base = t.r_base;
+  p.r_full = t.r_full;
+  p.r_cnt = t.r_cnt;
+  p.r_part = t.r_part;
+  p.n_rb = n_rb;
+  p.R = pa.r_min << j;
+  p.n_c = (n0 + p.R - 1) / p.R;
+  p.total = total;
+  plan_set_units(p, pa.wg_per_head, pa.tail_div);
+  // per range: row blocks with a part, with a full part; width on the line; then prefix sums over ranges
+  const int per_c = (p.n_c + kThreads - 1) / kThreads;  // <= 2
+  int width = 0, count = 0;
+  for (int i = 0; i < per_c; ++i) {
+    const int c = tid * per_c + i;
+    if (c < p.n_c) {
+      const int cnt = count_longer(t.prefix, n_rb, c * p.R);
+      const int full = count_longer(t.prefix, n_rb, (c + 1) * p.R - 1);
+      t.r_cnt[c] = cnt;
+      t.r_full[c] = full;
+      width += full * p.R + (t.prefix[cnt] - t.prefix[full]) - (cnt - full) * c * p.R;
+      count += cnt;
+    }
+  }
+  int tot_w, tot_c;
+  int wb = block_exclusive_scan(width, t.wave_tmp, &tot_w);
+  int cb = block_exclusive_scan(count, t.wave_tmp, &tot_c);
+  for (int i = 0; i < per_c; ++i) {
+    const int c = tid * per_c + i;
+    if (c < p.n_c) {
+      const int cnt = t.r_cnt[c], full = t.r_full[c];
+      t.r_base[c] = wb;
+      t.r_part[c] = cb;
+      wb += full * p.R + (t.prefix[cnt] - t.prefix[full]) - (cnt - full) * c * p.R;
+      cb += cnt;
+    }
+  }
+  if (tid == 0) {
+    t.r_base[p.n_c] = tot_w;
+    t.r_part[p.n_c] = tot_c;
+  }
+  __syncthreads();
+  return true;
+}
+
+// Partial results travel between workgroups that may sit on different XCDs, whose L2s are not
+// coherent with each other.  Cache-wide write-backs or invalidations per piece would cost far more
+// than the pieces themselves (and an invalidation throws the K/V tiles out of the L2), so every
+// access to a slot is a device-scope relaxed atomic of 8 bytes instead: the store writes through to
+// memory, the load does not hit a line another XCD may have changed.
+__device__ __forceinline__ void store_coherent(float *p, float a, float b) {
+  const uint64_t v = static_cast<uint64_t>(__float_as_uint(a)) | (static_cast<uint64_t>(__float_as_uint(b)) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 load_coherent(const float *p) {
+  const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float(static_cast<uint32_t>(v)), __uint_as_float(static_cast<uint32_t>(v >> 32)));
+}
+
+// Partial result of a piece: accumulator registers 2 x .. 2 x + 1 of d tile dt go to
+// [wave][dt * 8 + x][lane], so every store instruction of a wavefront writes 512 consecutive bytes.
+__device__ __forceinline__ void write_partial(const WaveState &w, float *o_slot, float *ml_slot, int hf) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
-  float4 *dst = reinterpret_cast<float4 *>(o_slot) + (wave * 16) * 64 + lane;
+  float *dst = o_slot + ((wave * 32) * 64 + lane) * 2;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int ri = 0; ri < 4; ++ri)
-      dst[(dt * 4 + ri) * 64] = make_float4(w.O[dt][4 * ri + 0], w.O[dt][4 * ri + 1], w.O[dt][4 * ri + 2], w.O[dt][4 * ri + 3]);
-  if (hf == 0) ml_slot[wave * 32 + (lane & 31)] = make_float2(w.m_run, l_tot);
+    for (int x = 0; x < 8; ++x) store_coherent(dst + (dt * 8 + x) * 128, w.O[dt][2 * x], w.O[dt][2 * x + 1]);
+  if (hf == 0) store_coherent(ml_slot + 2 * (wave * 32 + (lane & 31)), w.m_run, l_tot);
+}
+
+// Merge of the pieces of row block q, in the order of the line (so the result does not depend on
+// which workgroup runs it):  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s,  M = max_s m_s.
+__device__ __forceinline__ void merge_pieces(const AttnPlan &p, int q, const float *o_part, const float *ml_part,
+                                             const Column &c, uint16_t *__restrict__ out, float *__restrict__ lse_out,
+                                             int n_q_heads, int g, int G) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hf = lane >> 5;
+  const int col = wave * 32 + (lane & 31);
+  float m_max = kNoMax;
+  plan_for_each_piece(p, q, [&](int slot) { m_max = fmaxf(m_max, load_coherent(ml_part + (static_cast<int64_t>(slot) * 128 + col) * 2).x); });
+  f32x16 O[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+  float l = 0.f;
+  plan_for_each_piece(p, q, [&](int slot) {
+    const float2 ml = load_coherent(ml_part + (static_cast<int64_t>(slot) * 128 + col) * 2);
+    const float wgt = __builtin_amdgcn_exp2f(ml.x - m_max);  // 0 for a piece that saw no key of this column
+    l = fmaf(ml.y, wgt, l);
+    const float *src = o_part + static_cast<int64_t>(slot) * kPartFloats + ((wave * 32) * 64 + lane) * 2;
+    float2 v[32];  // all loads of a piece are issued before the first is used
+#pragma unroll
+    for (int x = 0; x < 32; ++x) v[x] = load_coherent(src + x * 128);
+#pragma unroll
+    for (int x = 0; x < 32; ++x) {
+      O[x >> 3][2 * (x & 7)] = fmaf(v[x].x, wgt, O[x >> 3][2 * (x & 7)]);
+      O[x >> 3][2 * (x & 7) + 1] = fmaf(v[x].y, wgt, O[x >> 3][2 * (x & 7) + 1]);
+    }
+  });
+  store_output(O, m_max, l, c, out, lse_out, n_q_heads, g, G, hf);
 }
 
 // ---------------------------------------------------------------------------
@@ -505,8 +630,8 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   static_assert(NWAVES * 64 == kThreads, "the plan code assumes 256 threads");
   __shared__ __attribute__((aligned(1024))) uint16_t k_lds[NS][TILE_ELEMS];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds[NS][TILE_ELEMS];
-  __shared__ int s_prefix[kPlanMaxBlocks + 1];
-  __shared__ int s_wave[NWAVES];
+  __shared__ PlanTables tables;
+  __shared__ int s_last, s_next;
 
   const int lane = threadIdx.x & 63;
   const int hf = lane >> 5;
@@ -514,38 +639,76 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   const int g = blockIdx.x % n_kv_heads;
   const int wg = blockIdx.x / n_kv_heads;
 
-  build_prefix(s_prefix, s_wave, row_pos, n_rows, n_kv, pa.n_rb, rows_per_block);
-  const Shares sh(s_prefix[pa.n_rb], pa.wg_per_head, pa.min_share);
-  if (wg >= sh.w_eff) return;  // uniform over the workgroup
-  const int lo = sh.lo(wg), hi = sh.lo(wg + 1);
-  if (lo >= hi) return;
+  unsigned long long *trace = (pa.trace != nullptr && threadIdx.x == 0) ? pa.trace + static_cast<size_t>(blockIdx.x) * kTraceWords : nullptr;
+  int n_trace = 0;
+  auto stamp = [&](unsigned long long tag) {
+    if (trace != nullptr && n_trace < kTraceWords) trace[n_trace++] = (wall_clock64() << 8) | tag;
+  };
+  stamp(1);
+  AttnPlan plan;
+  if (!build_plan(plan, tables, row_pos, n_rows, n_kv, rows_per_block, pa)) return;  // uniform over the launch, ruled out by the host
+  stamp(2);
 
   const ReadOffsets ro = make_read_offsets(lane);
   const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
   const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
   const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
-  const auto plan = make_dma_plan<NWAVES>(kv_row_elems);
+  const auto dma = make_dma_plan<NWAVES>(kv_row_elems);
   const uint32_t k_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&k_lds[0][0]));
   const uint32_t v_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&v_lds[0][0]));
   constexpr uint32_t kStageBytes = TILE_ELEMS * 2;
+  float *o_part = pa.o_part + static_cast<int64_t>(g) * pa.slot_cap * kPartFloats;
+  float *ml_part = pa.ml_part + static_cast<int64_t>(g) * pa.slot_cap * 256;
+  int *arrived = pa.arrived + g * (kPlanMaxBlocks + 2);
+  int *next_unit = arrived + kPlanMaxBlocks, *gone = next_unit + 1;
 
-  int q = block_of(s_prefix, pa.n_rb, lo);
+  // A piece counts its tiles on the row block once its partial result has reached memory (the stores
+  // write through, see store_coherent, and have completed when the wavefront's memory counter has
+  // drained); the workgroup that completes the count merges all pieces of the row block and leaves
+  // the counter at zero for the next launch.  Nobody waits for anybody.  The count of a piece is
+  // taken after the NEXT piece's kv loop, whose end drains the counter anyway, so the stores'
+  // latency is never waited for.
+  int pend_q = -1, pend_count = 0;
+  auto arrive_pending = [&]() {
+    if (pend_q < 0) return;  // uniform over the workgroup
+    const int n_tiles = plan_tiles_of(plan, pend_q);
+    __syncthreads();  // every wavefront's stores of that piece have completed
+    if (threadIdx.x == 0) {
+      const int done = __hip_atomic_fetch_add(&arrived[pend_q], pend_count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + pend_count;
+      s_last = (done == n_tiles) ? 1 : 0;
+      if (done == n_tiles) __hip_atomic_store(&arrived[pend_q], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    stamp(5);
+    if (s_last != 0) {
+      const int rb = pa.n_rb - 1 - pend_q;
+      const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
+                                    (threadIdx.x >> 6) * 32 + (lane & 31));
+      merge_pieces(plan, pend_q, o_part, ml_part, c, out, lse_out, n_q_heads, g, G);
+      stamp(6);
+    }
+    pend_q = -1;
+  };
+
+  // Units: the first W by workgroup index, every further one from the head's counter.  The counter
+  // is read when a unit starts and the answer used when it ends, so its latency is never waited for.
   int seg = 0;
-  for (int pos = lo; pos < hi; ++q, ++seg) {
-    const int base = s_prefix[q];
-    const int n_tiles = s_prefix[q + 1] - base;
-    const int t0 = pos - base;                 // this segment: tiles t0 .. t1-1 of row block rb
-    const int t1 = min(hi - base, n_tiles);
+  for (int unit = wg; unit < plan.n_units;) {
+    int fetched = 0;
+    if (threadIdx.x == 0)
+      fetched = pa.wg_per_head + __hip_atomic_fetch_add(next_unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    plan_for_each_segment(plan, unit, [&](int q, int t0, int t1, int slot) {
+    const int n_tiles = plan_tiles_of(plan, q);
     const bool whole = (t0 == 0) && (t1 == n_tiles);
     const int rb = pa.n_rb - 1 - q;
-    pos = base + t1;
-
     if (seg > 0) {
       // the previous segment's stores are out and every wavefront is done reading its last tile
       // before the LDS ring is refilled
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
     }
+    ++seg;
+    stamp(3);
     const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
                                   (threadIdx.x >> 6) * 32 + (lane & 31));
     bf16x8 qf[8];
@@ -563,7 +726,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t)
-      issue_tile_dma<NWAVES>(plan, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
+      issue_tile_dma<NWAVES>(dma, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
                              kv_row_elems, t0 + t, n_kv);
 
     const int my_tiles = min(t1, c.p_wmax / TK + 1);
@@ -577,7 +740,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
       __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
       {
         const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
-        issue_tile_dma<NWAVES>(plan, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
+        issue_tile_dma<NWAVES>(dma, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
                                kv_row_elems, i + NS - 1, n_kv);
       }
       if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
@@ -597,76 +760,36 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
         if (i0 + st < t1) tile_step(i0 + st, st);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is reused or released
+    stamp(4);
     if (whole) {
       const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
       store_output(w.O, w.m_run, l_tot, c, out, lse_out, n_q_heads, g, G, hf);
     } else {
-      const int64_t slot = 2 * static_cast<int64_t>(blockIdx.x) + (seg > 0 ? 1 : 0);
-      write_partial(w, pa.o_part + slot * kPartFloats, pa.ml_part + slot * 128, hf);
+      write_partial(w, o_part + static_cast<int64_t>(slot) * kPartFloats, ml_part + static_cast<int64_t>(slot) * 256, hf);
+    }
+    arrive_pending();  // the piece before this one: its stores completed while this one was computed
+    if (!whole) {
+      pend_q = q;
+      pend_count = t1 - t0;
+    }
+    });
+    if (threadIdx.x == 0) s_next = fetched;
+    __syncthreads();  // (the next write of s_next lies behind the barriers of the next unit's pieces)
+    unit = s_next;
+  }
+  if (pend_q >= 0) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    arrive_pending();
+  }
+  // the last workgroup of the head to leave puts the unit counter back to zero for the next launch
+  if (threadIdx.x == 0) {
+    const int left = __hip_atomic_fetch_add(gone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+    if (left == pa.wg_per_head) {
+      __hip_atomic_store(next_unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(gone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-}
-
-// Merge of the row blocks that were cut.  Same grid and same plan as the attention kernel; the
-// workgroup slot whose share contains a cut row block's last tile merges all of its pieces:
-//   O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s,   M = max_s m_s.
-// A piece that begins a workgroup's share sits in that workgroup's slot 0, a piece that begins
-// later (the share's last segment) in slot 1.
-__global__ __launch_bounds__(kThreads) void attn_combine_kernel(const int32_t *__restrict__ row_pos, int n_rows, int n_kv,
-                                                                uint16_t *__restrict__ out, float *__restrict__ lse_out,
-                                                                int n_q_heads, int n_kv_heads, int rows_per_block,
-                                                                PlanArgs pa) {
-  __shared__ int s_prefix[kPlanMaxBlocks + 1];
-  __shared__ int s_wave[kThreads / 64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int hf = lane >> 5;
-  const int G = n_q_heads / n_kv_heads;
-  const int g = blockIdx.x % n_kv_heads;
-  const int wg = blockIdx.x / n_kv_heads;
-
-  build_prefix(s_prefix, s_wave, row_pos, n_rows, n_kv, pa.n_rb, rows_per_block);
-  const Shares sh(s_prefix[pa.n_rb], pa.wg_per_head, pa.min_share);
-  if (wg >= sh.w_eff) return;
-  const int lo = sh.lo(wg), hi = sh.lo(wg + 1);
-  if (lo >= hi) return;
-  const int q = block_of(s_prefix, pa.n_rb, lo);
-  const int base = s_prefix[q];
-  if (base == lo) return;              // the share begins with the start of a row block: nothing to finish here
-  if (s_prefix[q + 1] > hi) return;    // the row block goes on into later shares: its last piece merges
-  const int w_first = sh.owner(base);
-  const int rb = pa.n_rb - 1 - q;
-  const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
-                                wave * 32 + (lane & 31));
-  const int col = wave * 32 + (lane & 31);
-  float m_max = kNoMax;
-  for (int wp = w_first; wp <= wg; ++wp) {
-    const int64_t slot = 2 * (static_cast<int64_t>(wp) * n_kv_heads + g) + (base > sh.lo(wp) ? 1 : 0);
-    m_max = fmaxf(m_max, pa.ml_part[slot * 128 + col].x);
-  }
-  f32x16 O[4];
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
-  float l = 0.f;
-  for (int wp = w_first; wp <= wg; ++wp) {
-    const int64_t slot = 2 * (static_cast<int64_t>(wp) * n_kv_heads + g) + (base > sh.lo(wp) ? 1 : 0);
-    const float2 ml = pa.ml_part[slot * 128 + col];
-    const float wgt = __builtin_amdgcn_exp2f(ml.x - m_max);  // 0 for a piece that saw no key of this column
-    l = fmaf(ml.y, wgt, l);
-    const float4 *src = reinterpret_cast<const float4 *>(pa.o_part + slot * kPartFloats) + (wave * 16) * 64 + lane;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int ri = 0; ri < 4; ++ri) {
-        const float4 x = src[(dt * 4 + ri) * 64];
-        O[dt][4 * ri + 0] = fmaf(x.x, wgt, O[dt][4 * ri + 0]);
-        O[dt][4 * ri + 1] = fmaf(x.y, wgt, O[dt][4 * ri + 1]);
-        O[dt][4 * ri + 2] = fmaf(x.z, wgt, O[dt][4 * ri + 2]);
-        O[dt][4 * ri + 3] = fmaf(x.w, wgt, O[dt][4 * ri + 3]);
-      }
-  }
-  store_output(O, m_max, l, c, out, lse_out, n_q_heads, g, G, hf);
+  stamp(7);
 }
 
 }  // namespace
@@ -687,22 +810,47 @@ int default_wg_per_head(const ifkv_ctx *ctx) {
   return w > 0 ? w : 1;
 }
 
+constexpr int kDefaultRangeTiles = 64;
+
 }  // namespace
 
-// Two partial slots (64 KiB of O + 1 KiB of statistics) per workgroup of the largest grid: fixed for
-// a layer shape, whatever the number of rows.
+constexpr int kDefaultTailDiv = 8;
+
+// Partial slots per kv head: three per kv tile of the longest cache the layer admits (what a launch
+// of 30 % of the rows needs with 64-tile ranges), at least 256 and at most 2048, plus those of the
+// short units at the end of a launch.  A launch that needs more lengthens its ranges by itself.
+int attention_mfma_slot_cap(const ifkv_ctx *ctx) {
+  const int64_t tiles = (ctx->desc.max_ctx + TK - 1) / TK;
+  const int64_t s = std::min<int64_t>(std::max<int64_t>(3 * tiles, 256), 2048);
+  return static_cast<int>(s) + plan_max_tail_units(default_wg_per_head(ctx), kDefaultTailDiv);
+}
+
+// Row blocks one launch may hold: the plan's tables, and in the worst case (ranges longer than the
+// cache) one part and one full unit per row block plus the short units must fit the slots.
+int attention_mfma_max_row_blocks(const ifkv_ctx *ctx) {
+  const int by_slots = (attention_mfma_slot_cap(ctx) - plan_max_tail_units(default_wg_per_head(ctx), kDefaultTailDiv)) / 2;
+  return std::min(kPlanMaxBlocks, by_slots);
+}
+
 size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx) {
-  const size_t slots = 2 * static_cast<size_t>(default_wg_per_head(ctx)) * ctx->desc.n_kv_heads;
+  const size_t slots = static_cast<size_t>(attention_mfma_slot_cap(ctx)) * ctx->desc.n_kv_heads;
   return align256(slots * kPartFloats * sizeof(float)) + align256(slots * 128 * sizeof(float2));
 }
 
-// Host-side bounds of a launch: the grid must fit the partial slots that were allocated and the
-// row blocks must fit the plan held in LDS.  Returns false (nothing launched) otherwise.
-bool attention_mfma_launch_fits(const ifkv_ctx *ctx, int wg_per_head, int64_t n_rb) {
-  if (wg_per_head < 1 || n_rb < 1 || n_rb > kPlanMaxBlocks) return false;
-  const size_t slots = 2 * static_cast<size_t>(wg_per_head) * ctx->desc.n_kv_heads;
-  const size_t need = align256(slots * kPartFloats * sizeof(float)) + align256(slots * 128 * sizeof(float2));
-  return ctx->scratch != nullptr && need <= ctx->scratch_bytes && wg_per_head <= default_wg_per_head(ctx);
+size_t attention_mfma_counter_bytes(const ifkv_ctx *ctx) {
+  return static_cast<size_t>(ctx->desc.n_kv_heads) * (kPlanMaxBlocks + 2) * sizeof(int);
+}
+
+// Host-side bounds of a launch against what was allocated.  Returns false (nothing launched) otherwise.
+bool attention_mfma_launch_fits(const ifkv_ctx *ctx, int wg_per_head, int64_t n_rb, int64_t n_kv, int r_min, int tail_div) {
+  if (wg_per_head < 1 || wg_per_head > default_wg_per_head(ctx)) return false;
+  if (tail_div < 1 || tail_div > kDefaultTailDiv || tail_div > r_min) return false;
+  if (n_rb < 1 || n_rb > attention_mfma_max_row_blocks(ctx)) return false;
+  if (ctx->scratch == nullptr || attention_mfma_scratch_bytes(ctx) > ctx->scratch_bytes) return false;
+  if (ctx->attn_arrived == nullptr) return false;
+  // the longest candidate range must cover the cache, so that the fallback (one part per row block) exists
+  const int64_t tiles = (n_kv + TK - 1) / TK;
+  return r_min >= 1 && (r_min & (r_min - 1)) == 0 && (static_cast<int64_t>(r_min) << (kPlanRangeChoices - 1)) >= tiles;
 }
 
 hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
@@ -714,18 +862,23 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
   const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
   int wg_per_head = default_wg_per_head(ctx);
   if (ctx->tune.attn_wg_per_head > 0 && ctx->tune.attn_wg_per_head < wg_per_head) wg_per_head = ctx->tune.attn_wg_per_head;
-  int64_t max_rb = kPlanMaxBlocks;
+  int64_t max_rb = attention_mfma_max_row_blocks(ctx);
   if (ctx->tune.attn_max_row_blocks > 0 && ctx->tune.attn_max_row_blocks < max_rb) max_rb = ctx->tune.attn_max_row_blocks;
-  const int min_share = ctx->tune.attn_min_share_tiles > 0 ? ctx->tune.attn_min_share_tiles : 8;
+  int r_min = ctx->tune.attn_range_tiles > 0 ? ctx->tune.attn_range_tiles : kDefaultRangeTiles;
+  const int64_t tiles = (n_kv + TK - 1) / TK;
+  while ((static_cast<int64_t>(r_min) << (kPlanRangeChoices - 1)) < tiles) r_min <<= 1;
 
-  // the slots live at the start of the context's scratch, laid out for the largest grid
-  const size_t slots_max = 2 * static_cast<size_t>(default_wg_per_head(ctx)) * d.n_kv_heads;
+  const size_t slots = static_cast<size_t>(attention_mfma_slot_cap(ctx)) * d.n_kv_heads;
   char *scratch = static_cast<char *>(ctx->scratch);
   PlanArgs pa;
   pa.wg_per_head = wg_per_head;
-  pa.min_share = min_share;
+  pa.r_min = r_min;
+  pa.tail_div = std::min(ctx->tune.attn_tail_div > 0 ? ctx->tune.attn_tail_div : kDefaultTailDiv, r_min);
+  pa.slot_cap = attention_mfma_slot_cap(ctx);
   pa.o_part = reinterpret_cast<float *>(scratch);
-  pa.ml_part = reinterpret_cast<float2 *>(scratch + align256(slots_max * kPartFloats * sizeof(float)));
+  pa.ml_part = reinterpret_cast<float *>(scratch + align256(slots * kPartFloats * sizeof(float)));
+  pa.arrived = ctx->attn_arrived;
+  pa.trace = reinterpret_cast<unsigned long long *>(ctx->tune.attn_trace);
 
   // More row blocks than one plan holds are served by several launches over consecutive row ranges
   // (rows are independent).  Launches of one stream run one after the other, so they share the slots.
@@ -735,7 +888,7 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
   for (int64_t r0 = 0; r0 < n_rows; r0 += rows_per_launch) {
     const int64_t nr = n_rows - r0 < rows_per_launch ? n_rows - r0 : rows_per_launch;
     pa.n_rb = static_cast<int>((nr + rpb - 1) / rpb);
-    if (!attention_mfma_launch_fits(ctx, wg_per_head, pa.n_rb)) return hipErrorInvalidValue;
+    if (!attention_mfma_launch_fits(ctx, wg_per_head, pa.n_rb, n_kv, r_min, pa.tail_div)) return hipErrorInvalidValue;
     const uint16_t *q_r = static_cast<const uint16_t *>(q_sel) + r0 * row_elems;
     uint16_t *out_r = static_cast<uint16_t *>(out) + r0 * row_elems;
     float *lse_r = lse_out != nullptr ? lse_out + r0 * d.n_q_heads : nullptr;
@@ -743,8 +896,6 @@ hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t
                        static_cast<int>(nr), static_cast<const uint16_t *>(k_cache),
                        static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), out_r, lse_r, d.n_q_heads,
                        d.n_kv_heads, scale_log2, rpb, pa);
-    hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(kThreads), 0, ctx->stream, row_pos + r0, static_cast<int>(nr),
-                       static_cast<int>(n_kv), out_r, lse_r, d.n_q_heads, d.n_kv_heads, rpb, pa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

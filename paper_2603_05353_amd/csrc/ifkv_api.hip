@@ -49,6 +49,21 @@ int ensure_scratch(ifkv_ctx *ctx) {
     (void)hipGetLastError();
     return fail(ctx, IFKV_ENOMEM, "scratch allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
   }
+  // stage 4's arrival counters live apart from the shared scratch (the other stages would overwrite
+  // them) and must read zero before the first launch; every launch leaves them at zero again
+  const size_t cbytes = ifkv::attention_counter_bytes(ctx);
+  if (cbytes > 0) {
+    void *c = nullptr;
+    e = hipMalloc(&c, cbytes);
+    if (e == hipSuccess) e = hipMemset(c, 0, cbytes);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (c != nullptr) (void)hipFree(c);
+      (void)hipFree(p);
+      return fail(ctx, IFKV_ENOMEM, "counter allocation of %zu bytes failed: %s", cbytes, hipGetErrorString(e));
+    }
+    ctx->attn_arrived = static_cast<int *>(c);
+  }
   ctx->scratch = p;
   ctx->scratch_bytes = bytes;
   return IFKV_OK;
@@ -124,6 +139,7 @@ int ifkv_create(ifkv_ctx **out, const ifkv_layer_desc *desc, void *hip_stream) {
 void ifkv_destroy(ifkv_ctx *ctx) {
   if (ctx == nullptr) return;
   if (ctx->scratch != nullptr) (void)hipFree(ctx->scratch);
+  if (ctx->attn_arrived != nullptr) (void)hipFree(ctx->attn_arrived);
   if (ctx->d_inv_freq != nullptr) (void)hipFree(ctx->d_inv_freq);
   delete ctx;
 }
@@ -373,13 +389,20 @@ int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value) {
     int *slot;
     int64_t hi;
   } knobs[] = {{"attn_wg_per_head", &ctx->tune.attn_wg_per_head, wg_max},
-               {"attn_min_share_tiles", &ctx->tune.attn_min_share_tiles, 1 << 20},
-               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 3072}};
+               {"attn_tail_div", &ctx->tune.attn_tail_div, 8},
+               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 1024},
+               {"attn_range_tiles", &ctx->tune.attn_range_tiles, 4096}};
+  if (std::strcmp(key, "attn_trace") == 0) {
+    ctx->tune.attn_trace = value;
+    return IFKV_OK;
+  }
   for (const Knob &k : knobs) {
     if (std::strcmp(key, k.name) != 0) continue;
     if (value < 0 || value > k.hi)
       return fail(ctx, IFKV_EINVAL, "set_tuning: %s=%lld is outside [0, %lld]", key, static_cast<long long>(value),
                   static_cast<long long>(k.hi));
+    if ((k.slot == &ctx->tune.attn_range_tiles || k.slot == &ctx->tune.attn_tail_div) && (value & (value - 1)) != 0)
+      return fail(ctx, IFKV_EINVAL, "set_tuning: %s=%lld is not a power of two", key, static_cast<long long>(value));
     *k.slot = static_cast<int>(value);
     return IFKV_OK;
   }

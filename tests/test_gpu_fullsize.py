@@ -116,7 +116,7 @@ def rows_agree(a, b, rel=0.02):
 
 
 # other ways of cutting the same launch into workgroup shares
-OTHER_CUTS = {"attn_wg_per_head": 37, "attn_min_share_tiles": 1}
+OTHER_CUTS = {"attn_wg_per_head": 37, "attn_range_tiles": 32, "attn_tail_div": 2}
 
 
 def test_splice_and_attention_sampled_rows(run):

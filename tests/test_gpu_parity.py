@@ -374,8 +374,8 @@ ATTN_SHAPES = [
     ([1], [0], 8, 2), ([63], "all", 8, 2), ([64], [0, 63], 8, 2), ([65], [64], 8, 2), ([65], "all", 8, 2),
     ([128, 100], 50, 32, 1), ([300], 200, 8, 8), ([129], [0, 1, 2, 127, 128], 28, 4),
 ]
-# launch shapes: the library's own; every row block cut between as many workgroups as there are tiles
-FINE_CUTS = {"attn_min_share_tiles": 1}
+# launch shapes: the library's own; kv ranges of one tile, so that every row block is cut at every tile
+FINE_CUTS = {"attn_range_tiles": 1}
 
 
 @pytest.mark.parametrize("lens,rows,hq,hkv", ATTN_SHAPES,
@@ -391,17 +391,18 @@ def test_attention_mfma_shapes(lens, rows, hq, hkv, tuning):
     attention_case(spec, np.asarray(rows, dtype=np.int64), tuning=tuning)
 
 
-# How the (row block, kv tile) line is cut into workgroup shares is the library's choice; every
-# choice must give the same rows.  100 kv tiles, 30 row blocks.
+# How the (row block, kv tile) line is laid out and cut into workgroup shares is the library's choice;
+# every choice must give the same rows.  100 kv tiles, 30 row blocks.
 CUT_TUNINGS = [
     ("default", None),
     ("one-workgroup-per-head", {"attn_wg_per_head": 1}),
-    ("3-workgroups", {"attn_wg_per_head": 3, "attn_min_share_tiles": 1}),
-    ("7-workgroups", {"attn_wg_per_head": 7, "attn_min_share_tiles": 1}),
-    ("single-tile-shares", {"attn_min_share_tiles": 1}),
-    ("40-tile-shares", {"attn_min_share_tiles": 40}),
+    ("3-workgroups-8-tile-ranges", {"attn_wg_per_head": 3, "attn_range_tiles": 8}),
+    ("7-workgroups-2-tile-ranges", {"attn_wg_per_head": 7, "attn_range_tiles": 2, "attn_tail_div": 2}),
+    ("single-tile-ranges", {"attn_range_tiles": 1}),
+    ("16-tile-ranges", {"attn_range_tiles": 16}),
+    ("ranges-longer-than-the-cache", {"attn_range_tiles": 128, "attn_tail_div": 1}),
     ("2-row-blocks-per-launch", {"attn_max_row_blocks": 2}),
-    ("3-row-blocks-per-launch-fine", {"attn_max_row_blocks": 3, "attn_min_share_tiles": 1}),
+    ("3-row-blocks-per-launch-4-tile-ranges", {"attn_max_row_blocks": 3, "attn_range_tiles": 4, "attn_tail_div": 4}),
 ]
 
 
