@@ -27,7 +27,7 @@ EXPORTS = (
     "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
     "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
     "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",   # include/ifkv_calibrate.h
-    "ifkv_set_tuning", "ifkv_attention_plan",                                # include/ifkv_debug.h
+    "ifkv_set_tuning",                                                       # include/ifkv_debug.h
 )
 
 
@@ -94,10 +94,6 @@ def load_library() -> C.CDLL:
     lib.ifkv_mfma_probe_sink_floats.restype = i64
     lib.ifkv_set_tuning.argtypes = [vp, C.c_char_p, i64]
     lib.ifkv_set_tuning.restype = C.c_int
-    i32p = C.POINTER(C.c_int32)
-    lib.ifkv_attention_plan.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, i64, i32p, i64,
-                                        C.POINTER(i64), i32p]
-    lib.ifkv_attention_plan.restype = i64
     _lib = lib
     return lib
 

@@ -138,11 +138,6 @@ size_t attention_scratch_bytes(const ifkv_ctx *ctx) {
   return generic ? 0 : attention_mfma_scratch_bytes(ctx);
 }
 
-size_t attention_counter_bytes(const ifkv_ctx *ctx) {
-  const bool generic = (ctx->desc.flags & IFKV_FLAG_FORCE_GENERIC) || !attention_mfma_supported(ctx);
-  return generic ? 0 : attention_mfma_counter_bytes(ctx);
-}
-
 hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out, float *lse_out) {
   if (n_rows <= 0) return hipSuccess;

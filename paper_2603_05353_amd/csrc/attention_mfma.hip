@@ -25,21 +25,17 @@
 // product -- which needs eight kv values of one d column per lane, the strided axis -- is read
 // with the LDS transpose loads (ds_read_b64_tr_b16), two per operand.
 //
-// Work distribution.  A row block at position p costs p/64 + 1 tiles, so the blocks of one launch
-// differ in length by two orders of magnitude while the chip holds only 512 of these workgroups at
-// a time (two per CU): handing out whole row blocks leaves an eighth of the machine idle at the
-// end of a launch, and cutting the blocks' tiles into equal contiguous shares makes every workgroup
-// stream its own stretch of K/V through the fabric (6.8 GB per launch instead of 0.8 GB measured at
-// 32K context).  The launch therefore has a fixed number of workgroups per kv head that walk the
-// (kv range, row block, tile) line of attention_plan.h in step: at any time they read the same few
-// K/V tiles, and all end together.  Pieces that are not a whole row block leave their unnormalised
-// O, reference max and sum in a scratch slot and count their tiles on the row block; the workgroup
-// that completes the count merges the pieces.  Every workgroup derives the plan by itself from
-// row_pos: no extra launch, no host knowledge of the positions, and nobody waits for anybody.
+// Work distribution.  One workgroup per (kv head, row block), dispatched longest row block first,
+// so that the short ones fill the end of the launch; all workgroups of a head start at tile 0 and
+// walk the kv axis together, which lets the L2 serve most tile fetches (0.8 GB reach the fabric per
+// launch at 32K context; cutting the blocks' tiles into equal contiguous shares per workgroup
+// instead, which balances the launch perfectly on paper, sends 6.8 GB through the fabric and is
+// slower).  Launches with fewer row blocks than the chip has workgroup slots are cut along the kv
+// axis: each part leaves its unnormalised O, reference max and sum in scratch and
+// attn_combine_kernel merges them.
 #include <algorithm>
 
 #include "attention_common.h"
-#include "attention_plan.h"
 #include "ifkv_device.h"
 
 namespace ifkv {
@@ -389,408 +385,179 @@ __device__ __forceinline__ void store_output(const f32x16 (&O)[4], float m_ref, 
         ok ? 0.6931471805599453f * (m_ref + __log2f(l_tot)) : 0.f;
 }
 
-// ---------------------------------------------------------------------------
-// The plan (attention_plan.h) built in LDS by every workgroup for itself: no extra launch, no host
-// knowledge of the positions.
-// ---------------------------------------------------------------------------
-constexpr int kThreads = 256;
+template <int NWAVES>
+__device__ __forceinline__ int block_tiles(int p_wmax, int *s_pmax) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) s_pmax[wave] = p_wmax;
+  __syncthreads();
+  int p_bmax = 0;
+#pragma unroll
+  for (int w = 0; w < NWAVES; ++w) p_bmax = max(p_bmax, s_pmax[w]);
+  return p_bmax / TK + 1;
+}
 
-struct PlanArgs {
-  int n_rb;             // row blocks of this launch (<= kPlanMaxBlocks)
-  int wg_per_head;      // workgroups per kv head
-  int tail_div;         // the short units at the end of the line are 1/tail_div of a kv range
-  int r_min;            // smallest kv range, in tiles (a power of two)
-  int slot_cap;         // partial slots per kv head
-  float *o_part;        // [n_kv_heads * slot_cap] x [128 * 128]: unnormalised O, see write_partial
-  float *ml_part;       // [n_kv_heads * slot_cap] x [128] x 2: (reference max in the log2 domain, sum) per query column
-  int *arrived;         // [n_kv_heads][kPlanMaxBlocks + 2]: tiles of a shared row block that are done, then the
-                        // units handed out beyond the first W and the workgroups that have left; zero between launches
-  unsigned long long *trace;  // tuning aid, normally null: [grid][kTraceWords] time stamps of thread 0 (100 MHz counter)
-};
-constexpr int kTraceWords = 64;
-constexpr size_t kPartFloats = 128 * D;  // O floats per partial slot
-
-struct PlanTables {
-  int prefix[kPlanMaxBlocks + 1];
-  int r_base[kPlanMaxRanges + 1];
-  int r_full[kPlanMaxRanges];
-  int r_cnt[kPlanMaxRanges];
-  int r_part[kPlanMaxRanges + 1];
-  int wave_tmp[kThreads / 64][kPlanRangeChoices + 1];
+// ---------------------------------------------------------------------------
+// Split over the kv axis.  Row blocks differ in length by two orders of magnitude (a row at
+// position p costs p keys), and a launch has only a few blocks per CU, so the longest blocks set
+// the finish time.  With `part_tiles` < the tile count of a row block, the block's kv range is
+// divided into parts of part_tiles tiles, one workgroup each (blockIdx.z); each part keeps its own
+// running (max, sum) and unnormalised O and writes them to scratch, and attn_combine_kernel merges
+// the parts of every row that was split.  Row blocks that fit in one part write their output
+// directly, as without the split.
+// ---------------------------------------------------------------------------
+struct SplitPlan {
+  int part_tiles;     // kv tiles per part (>= number of tiles of the cache: no split)
+  float *o_part;      // [parts][n_rows][H_q][D] unnormalised O
+  float2 *ml_part;    // [parts][n_rows][H_q] (reference max in the log2 domain, sum)
+  int *block_tiles;   // [row blocks] tile count of each row block (written by part 0)
 };
 
-// Exclusive prefix of one value per thread over the workgroup (thread order); *total gets the sum.
-// Every thread must call; ends with a barrier, so the scratch row can be reused right away.
-__device__ __forceinline__ int block_exclusive_scan(int v, int (*wave_tmp)[kPlanRangeChoices + 1], int *total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int incl = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int u = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += u;
-  }
-  if (lane == 63) wave_tmp[wave][kPlanRangeChoices] = incl;
-  __syncthreads();
-  int base = incl - v, sum = 0;
-#pragma unroll
-  for (int w = 0; w < kThreads / 64; ++w) {
-    const int x = wave_tmp[w][kPlanRangeChoices];
-    if (w < wave) base += x;
-    sum += x;
-  }
-  *total = sum;
-  __syncthreads();
-  return base;
-}
-
-// tiles of row block q (descending length order): that of its last row, positions clamped into the
-// cache (rows outside it produce zeros and never extend a block)
-__device__ __forceinline__ int block_tiles_of(const int32_t *__restrict__ row_pos, int n_rows, int n_kv, int n_rb,
-                                              int rows_per_block, int q) {
-  const int rb = n_rb - 1 - q;
-  const int last = min((rb + 1) * rows_per_block, n_rows) - 1;
-  return min(max(row_pos[last], 0), n_kv - 1) / TK + 1;
-}
-
-// number of row blocks with more than x tiles (tile counts do not increase with q)
-__device__ __forceinline__ int count_longer(const int *prefix, int n_rb, int x) {
-  int a = 0, b = n_rb;  // blocks [0, a) are longer, blocks [b, n_rb) are not
-  while (a < b) {
-    const int mid = (a + b) >> 1;
-    if (prefix[mid + 1] - prefix[mid] > x) a = mid + 1; else b = mid;
-  }
-  return a;
-}
-
-// Every thread of the workgroup must call this.  Returns false (for every thread) if the launch
-// does not fit the slots, which the host rules out before launching.
-__device__ __forceinline__ bool build_plan(AttnPlan &p, PlanTables &t, const int32_t *__restrict__ row_pos, int n_rows,
-                                           int n_kv, int rows_per_block, const PlanArgs &pa) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n_rb = pa.n_rb;
-  const int lg_min = 31 - __clz(pa.r_min);
-  // tiles per row block: prefix sums, and the number of parts for every candidate range length
-  const int per = (n_rb + kThreads - 1) / kThreads;
-  const int q0 = tid * per;
-  int sum = 0;
-  int parts[kPlanRangeChoices];
-#pragma unroll
-  for (int j = 0; j < kPlanRangeChoices; ++j) parts[j] = 0;
-  for (int i = 0; i < per; ++i) {
-    const int q = q0 + i;
-    if (q < n_rb) {
-      const int n = block_tiles_of(row_pos, n_rows, n_kv, n_rb, rows_per_block, q);
-      sum += n;
-#pragma unroll
-      for (int j = 0; j < kPlanRangeChoices; ++j) parts[j] += (n + (pa.r_min << j) - 1) >> (lg_min + j);
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < kPlanRangeChoices; ++j) {
-    const int s = wave_sum_i(parts[j]);
-    if (lane == 0) t.wave_tmp[wave][j] = s;
-  }
-  int total;
-  int base = block_exclusive_scan(sum, t.wave_tmp, &total);  // its first barrier also publishes the part counts
-  for (int i = 0; i < per; ++i) {  // second walk: the loads hit the cache this time
-    const int q = q0 + i;
-    if (q < n_rb) {
-      t.prefix[q] = base;
-      base += block_tiles_of(row_pos, n_rows, n_kv, n_rb, rows_per_block, q);
-    }
-  }
-  if (tid == 0) t.prefix[n_rb] = total;
-#pragma unroll
-  for (int j = 0; j < kPlanRangeChoices; ++j) {
-    int s = 0;
-#pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) s += t.wave_tmp[w][j];
-    parts[j] = s;
-  }
-  __syncthreads();
-  const int n0 = t.prefix[1];
-  const int j = plan_choose_range(parts, n0, total, pa.r_min, pa.wg_per_head, pa.tail_div, pa.slot_cap);
-  if (j < 0) return false;
-  p.prefix = t.prefix;
-  p.r_base = t.r_base;
-  p.r_full = t.r_full;
-  p.r_cnt = t.r_cnt;
-  p.r_part = t.r_part;
-  p.n_rb = n_rb;
-  p.R = pa.r_min << j;
-  p.n_c = (n0 + p.R - 1) / p.R;
-  p.total = total;
-  plan_set_units(p, pa.wg_per_head, pa.tail_div);
-  // per range: row blocks with a part, with a full part; width on the line; then prefix sums over ranges
-  const int per_c = (p.n_c + kThreads - 1) / kThreads;  // <= 2
-  int width = 0, count = 0;
-  for (int i = 0; i < per_c; ++i) {
-    const int c = tid * per_c + i;
-    if (c < p.n_c) {
-      const int cnt = count_longer(t.prefix, n_rb, c * p.R);
-      const int full = count_longer(t.prefix, n_rb, (c + 1) * p.R - 1);
-      t.r_cnt[c] = cnt;
-      t.r_full[c] = full;
-      width += full * p.R + (t.prefix[cnt] - t.prefix[full]) - (cnt - full) * c * p.R;
-      count += cnt;
-    }
-  }
-  int tot_w, tot_c;
-  int wb = block_exclusive_scan(width, t.wave_tmp, &tot_w);
-  int cb = block_exclusive_scan(count, t.wave_tmp, &tot_c);
-  for (int i = 0; i < per_c; ++i) {
-    const int c = tid * per_c + i;
-    if (c < p.n_c) {
-      const int cnt = t.r_cnt[c], full = t.r_full[c];
-      t.r_base[c] = wb;
-      t.r_part[c] = cb;
-      wb += full * p.R + (t.prefix[cnt] - t.prefix[full]) - (cnt - full) * c * p.R;
-      cb += cnt;
-    }
-  }
-  if (tid == 0) {
-    t.r_base[p.n_c] = tot_w;
-    t.r_part[p.n_c] = tot_c;
-  }
-  __syncthreads();
-  return true;
-}
-
-// Partial results travel between workgroups that may sit on different XCDs, whose L2s are not
-// coherent with each other.  Cache-wide write-backs or invalidations per piece would cost far more
-// than the pieces themselves (and an invalidation throws the K/V tiles out of the L2), so every
-// access to a slot is a device-scope relaxed atomic of 8 bytes instead: the store writes through to
-// memory, the load does not hit a line another XCD may have changed.
-__device__ __forceinline__ void store_coherent(float *p, float a, float b) {
-  const uint64_t v = static_cast<uint64_t>(__float_as_uint(a)) | (static_cast<uint64_t>(__float_as_uint(b)) << 32);
-  __hip_atomic_store(reinterpret_cast<uint64_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 load_coherent(const float *p) {
-  const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__uint_as_float(static_cast<uint32_t>(v)), __uint_as_float(static_cast<uint32_t>(v >> 32)));
-}
-
-// Partial result of a piece: accumulator registers 2 x .. 2 x + 1 of d tile dt go to
-// [wave][dt * 8 + x][lane], so every store instruction of a wavefront writes 512 consecutive bytes.
-__device__ __forceinline__ void write_partial(const WaveState &w, float *o_slot, float *ml_slot, int hf) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__device__ __forceinline__ void write_partial(const WaveState &w, const Column &c, const SplitPlan &sp, int part,
+                                              int n_rows, int n_q_heads, int g, int G, int hf) {
+  if (!c.col_valid) return;
   const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
-  float *dst = o_slot + ((wave * 32) * 64 + lane) * 2;
+  const int64_t slot = (static_cast<int64_t>(part) * n_rows + c.row) * n_q_heads + g * G + c.hh;
+  float *orow = sp.o_part + slot * D;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int x = 0; x < 8; ++x) store_coherent(dst + (dt * 8 + x) * 128, w.O[dt][2 * x], w.O[dt][2 * x + 1]);
-  if (hf == 0) store_coherent(ml_slot + 2 * (wave * 32 + (lane & 31)), w.m_run, l_tot);
+    for (int ri = 0; ri < 4; ++ri) {
+      float4 x = make_float4(w.O[dt][4 * ri + 0], w.O[dt][4 * ri + 1], w.O[dt][4 * ri + 2], w.O[dt][4 * ri + 3]);
+      *reinterpret_cast<float4 *>(orow + 32 * dt + 8 * ri + 4 * hf) = x;
+    }
+  if (hf == 0) sp.ml_part[slot] = make_float2(w.m_run, l_tot);
 }
 
-// Merge of the pieces of row block q, in the order of the line (so the result does not depend on
-// which workgroup runs it):  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s,  M = max_s m_s.
-__device__ __forceinline__ void merge_pieces(const AttnPlan &p, int q, const float *o_part, const float *ml_part,
-                                             const Column &c, uint16_t *__restrict__ out, float *__restrict__ lse_out,
-                                             int n_q_heads, int g, int G) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int hf = lane >> 5;
-  const int col = wave * 32 + (lane & 31);
-  float m_max = kNoMax;
-  plan_for_each_piece(p, q, [&](int slot) { m_max = fmaxf(m_max, load_coherent(ml_part + (static_cast<int64_t>(slot) * 128 + col) * 2).x); });
-  f32x16 O[4];
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
-  float l = 0.f;
-  plan_for_each_piece(p, q, [&](int slot) {
-    const float2 ml = load_coherent(ml_part + (static_cast<int64_t>(slot) * 128 + col) * 2);
-    const float wgt = __builtin_amdgcn_exp2f(ml.x - m_max);  // 0 for a piece that saw no key of this column
-    l = fmaf(ml.y, wgt, l);
-    const float *src = o_part + static_cast<int64_t>(slot) * kPartFloats + ((wave * 32) * 64 + lane) * 2;
-    float2 v[32];  // all loads of a piece are issued before the first is used
-#pragma unroll
-    for (int x = 0; x < 32; ++x) v[x] = load_coherent(src + x * 128);
-#pragma unroll
-    for (int x = 0; x < 32; ++x) {
-      O[x >> 3][2 * (x & 7)] = fmaf(v[x].x, wgt, O[x >> 3][2 * (x & 7)]);
-      O[x >> 3][2 * (x & 7) + 1] = fmaf(v[x].y, wgt, O[x >> 3][2 * (x & 7) + 1]);
+// One wavefront per (row, head) of a split row block: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+__global__ __launch_bounds__(256) void attn_combine_kernel(SplitPlan sp, const int32_t *__restrict__ row_pos,
+                                                           int n_rows, int n_kv, int n_q_heads, int rows_per_block,
+                                                           uint16_t *__restrict__ out, float *__restrict__ lse_out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t item = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int row = static_cast<int>(item / n_q_heads), head = static_cast<int>(item - static_cast<int64_t>(row) * n_q_heads);
+  if (row >= n_rows) return;
+  const int n_tiles = sp.block_tiles[row / rows_per_block];
+  const int n_parts = (n_tiles + sp.part_tiles - 1) / sp.part_tiles;
+  if (n_parts <= 1) return;  // written directly by the attention kernel
+  const int p = row_pos[row];
+  const bool in_range = p >= 0 && p < n_kv;
+  float m_max = -INFINITY;
+  for (int s = 0; s < n_parts; ++s)
+    m_max = fmaxf(m_max, sp.ml_part[(static_cast<int64_t>(s) * n_rows + row) * n_q_heads + head].x);
+  float l = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int s = 0; s < n_parts; ++s) {
+    const int64_t slot = (static_cast<int64_t>(s) * n_rows + row) * n_q_heads + head;
+    const float2 ml = sp.ml_part[slot];
+    if (ml.y > 0.f) {  // a part whose keys all lie behind this row's position holds a zero sum
+      const float wgt = __builtin_amdgcn_exp2f(ml.x - m_max);
+      const float2 o = *reinterpret_cast<const float2 *>(sp.o_part + slot * D + 2 * lane);
+      l += ml.y * wgt;
+      o0 += o.x * wgt;
+      o1 += o.y * wgt;
     }
-  });
-  store_output(O, m_max, l, c, out, lse_out, n_q_heads, g, G, hf);
+  }
+  const float inv = in_range && l > 0.f ? 1.f / l : 0.f;
+  const int64_t q = (static_cast<int64_t>(row) * n_q_heads + head);
+  *reinterpret_cast<uint32_t *>(out + q * D + 2 * lane) = pack_bf16x2(o0 * inv, o1 * inv);
+  if (lse_out != nullptr && lane == 0)
+    lse_out[q] = in_range && l > 0.f ? 0.6931471805599453f * (m_max + __log2f(l)) : 0.f;
 }
 
 // ---------------------------------------------------------------------------
 // NWAVES wavefronts, ring of NS LDS stages filled by direct global->LDS loads NS-1 tiles ahead.
-// blockIdx.x = w * n_kv_heads + g: consecutive workgroup ids go to consecutive XCDs, so with 8 kv
-// heads all workgroups of a head share one XCD's L2.
 // ---------------------------------------------------------------------------
 template <int NWAVES, int NS>
 __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ row_pos, int n_rows,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache, int n_kv,
     uint16_t *__restrict__ out, float *__restrict__ lse_out, int n_q_heads, int n_kv_heads, float scale_log2,
-    int rows_per_block, PlanArgs pa) {
-  static_assert(NWAVES * 64 == kThreads, "the plan code assumes 256 threads");
+    int rows_per_block, SplitPlan sp) {
   __shared__ __attribute__((aligned(1024))) uint16_t k_lds[NS][TILE_ELEMS];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds[NS][TILE_ELEMS];
-  __shared__ PlanTables tables;
-  __shared__ int s_last, s_next;
+  __shared__ int s_pmax[NWAVES];
 
   const int lane = threadIdx.x & 63;
   const int hf = lane >> 5;
   const int G = n_q_heads / n_kv_heads;
-  const int g = blockIdx.x % n_kv_heads;
-  const int wg = blockIdx.x / n_kv_heads;
-
-  unsigned long long *trace = (pa.trace != nullptr && threadIdx.x == 0) ? pa.trace + static_cast<size_t>(blockIdx.x) * kTraceWords : nullptr;
-  int n_trace = 0;
-  auto stamp = [&](unsigned long long tag) {
-    if (trace != nullptr && n_trace < kTraceWords) trace[n_trace++] = (wall_clock64() << 8) | tag;
-  };
-  stamp(1);
-  AttnPlan plan;
-  if (!build_plan(plan, tables, row_pos, n_rows, n_kv, rows_per_block, pa)) return;  // uniform over the launch, ruled out by the host
-  stamp(2);
-
+  const int g = blockIdx.x;
+  const int rb = gridDim.y - 1 - blockIdx.y;  // longest prefixes are dispatched first
+  const int part = blockIdx.z;
+  const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
+                                (threadIdx.x >> 6) * 32 + (lane & 31));
+  bf16x8 qf[8];
+  load_q_frags(qf, q_sel, c, hf);
+  const int n_tiles = block_tiles<NWAVES>(c.p_wmax, s_pmax);
+  // this workgroup's share of the kv axis: tiles t0 .. t1-1 (the whole range unless the block is split)
+  const int t0 = part * sp.part_tiles;
+  const int t1 = min(n_tiles, t0 + sp.part_tiles);
+  if (t0 >= n_tiles) return;  // nothing left for this part (uniform over the workgroup)
+  const bool split = n_tiles > sp.part_tiles;
+  if (part == 0 && g == 0 && threadIdx.x == 0 && sp.block_tiles != nullptr) sp.block_tiles[rb] = n_tiles;
   const ReadOffsets ro = make_read_offsets(lane);
+
   const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
   const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
   const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
-  const auto dma = make_dma_plan<NWAVES>(kv_row_elems);
+  const auto plan = make_dma_plan<NWAVES>(kv_row_elems);
+
   const uint32_t k_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&k_lds[0][0]));
   const uint32_t v_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&v_lds[0][0]));
   constexpr uint32_t kStageBytes = TILE_ELEMS * 2;
-  float *o_part = pa.o_part + static_cast<int64_t>(g) * pa.slot_cap * kPartFloats;
-  float *ml_part = pa.ml_part + static_cast<int64_t>(g) * pa.slot_cap * 256;
-  int *arrived = pa.arrived + g * (kPlanMaxBlocks + 2);
-  int *next_unit = arrived + kPlanMaxBlocks, *gone = next_unit + 1;
 
-  // A piece counts its tiles on the row block once its partial result has reached memory (the stores
-  // write through, see store_coherent, and have completed when the wavefront's memory counter has
-  // drained); the workgroup that completes the count merges all pieces of the row block and leaves
-  // the counter at zero for the next launch.  Nobody waits for anybody.  The count of a piece is
-  // taken after the NEXT piece's kv loop, whose end drains the counter anyway, so the stores'
-  // latency is never waited for.
-  int pend_q = -1, pend_count = 0;
-  auto arrive_pending = [&]() {
-    if (pend_q < 0) return;  // uniform over the workgroup
-    const int n_tiles = plan_tiles_of(plan, pend_q);
-    __syncthreads();  // every wavefront's stores of that piece have completed
-    if (threadIdx.x == 0) {
-      const int done = __hip_atomic_fetch_add(&arrived[pend_q], pend_count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + pend_count;
-      s_last = (done == n_tiles) ? 1 : 0;
-      if (done == n_tiles) __hip_atomic_store(&arrived[pend_q], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  WaveState w;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) w.O[dt][r] = 0.f;
+  w.m_run = kNoMax;
+  w.l_run = 0.f;
+
+  // Tiles t0 .. t0+NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
+  // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    issue_tile_dma<NWAVES>(plan, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
+                           kv_row_elems, t0 + t, n_kv);
+
+  const int my_tiles = min(t1, c.p_wmax / TK + 1);
+  // One tile.  `st` is a compile-time constant at every call (the loop below is unrolled over the
+  // ring), so the LDS stage base folds into the immediate offset of every LDS read and the reads
+  // cost no address arithmetic.
+  auto tile_step = [&](int i, int st) {
+    // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
+    // (loads complete in order; the query loads issued before them are therefore complete too)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
+    __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
+    {
+      const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
+      issue_tile_dma<NWAVES>(plan, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
+                             kv_row_elems, i + NS - 1, n_kv);
     }
-    __syncthreads();
-    stamp(5);
-    if (s_last != 0) {
-      const int rb = pa.n_rb - 1 - pend_q;
-      const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
-                                    (threadIdx.x >> 6) * 32 + (lane & 31));
-      merge_pieces(plan, pend_q, o_part, ml_part, c, out, lse_out, n_q_heads, g, G);
-      stamp(6);
+    if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
+      f32x16 S[2];
+      qk_tile(S, k_lds[st], qf, ro);
+      VFrags vf;
+      pv_preload(vf, v_lds[st], ro);
+      row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
+      PTile P;
+      exp_tile(S, w, P, scale_log2);
+      pv_tile(P, vf, w, v_lds[st], ro);
     }
-    pend_q = -1;
   };
-
-  // Units: the first W by workgroup index, every further one from the head's counter.  The counter
-  // is read when a unit starts and the answer used when it ends, so its latency is never waited for.
-  int seg = 0;
-  for (int unit = wg; unit < plan.n_units;) {
-    int fetched = 0;
-    if (threadIdx.x == 0)
-      fetched = pa.wg_per_head + __hip_atomic_fetch_add(next_unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    plan_for_each_segment(plan, unit, [&](int q, int t0, int t1, int slot) {
-    const int n_tiles = plan_tiles_of(plan, q);
-    const bool whole = (t0 == 0) && (t1 == n_tiles);
-    const int rb = pa.n_rb - 1 - q;
-    if (seg > 0) {
-      // the previous segment's stores are out and every wavefront is done reading its last tile
-      // before the LDS ring is refilled
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-    }
-    ++seg;
-    stamp(3);
-    const Column c = setup_column(row_pos, n_rows, n_kv, rb * rows_per_block, rows_per_block, G, g, n_q_heads,
-                                  (threadIdx.x >> 6) * 32 + (lane & 31));
-    bf16x8 qf[8];
-    load_q_frags(qf, q_sel, c, hf);
-
-    WaveState w;
+  for (int i0 = t0; i0 < t1; i0 += NS) {
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) w.O[dt][r] = 0.f;
-    w.m_run = kNoMax;
-    w.l_run = 0.f;
-
-    // Tiles t0 .. t0+NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
-    // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
-#pragma unroll
-    for (int t = 0; t < NS - 1; ++t)
-      issue_tile_dma<NWAVES>(dma, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
-                             kv_row_elems, t0 + t, n_kv);
-
-    const int my_tiles = min(t1, c.p_wmax / TK + 1);
-    // One tile.  `st` is a compile-time constant at every call (the loop below is unrolled over the
-    // ring), so the LDS stage base folds into the immediate offset of every LDS read and the reads
-    // cost no address arithmetic.
-    auto tile_step = [&](int i, int st) {
-      // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
-      // (loads complete in order; the query loads issued before them are therefore complete too)
-      __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
-      __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
-      {
-        const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
-        issue_tile_dma<NWAVES>(dma, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
-                               kv_row_elems, i + NS - 1, n_kv);
-      }
-      if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
-        f32x16 S[2];
-        qk_tile(S, k_lds[st], qf, ro);
-        VFrags vf;
-        pv_preload(vf, v_lds[st], ro);
-        row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
-        PTile P;
-        exp_tile(S, w, P, scale_log2);
-        pv_tile(P, vf, w, v_lds[st], ro);
-      }
-    };
-    for (int i0 = t0; i0 < t1; i0 += NS) {
-#pragma unroll
-      for (int st = 0; st < NS; ++st)
-        if (i0 + st < t1) tile_step(i0 + st, st);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is reused or released
-    stamp(4);
-    if (whole) {
-      const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
-      store_output(w.O, w.m_run, l_tot, c, out, lse_out, n_q_heads, g, G, hf);
-    } else {
-      write_partial(w, o_part + static_cast<int64_t>(slot) * kPartFloats, ml_part + static_cast<int64_t>(slot) * 256, hf);
-    }
-    arrive_pending();  // the piece before this one: its stores completed while this one was computed
-    if (!whole) {
-      pend_q = q;
-      pend_count = t1 - t0;
-    }
-    });
-    if (threadIdx.x == 0) s_next = fetched;
-    __syncthreads();  // (the next write of s_next lies behind the barriers of the next unit's pieces)
-    unit = s_next;
+    for (int st = 0; st < NS; ++st)
+      if (i0 + st < t1) tile_step(i0 + st, st);
   }
-  if (pend_q >= 0) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    arrive_pending();
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is released
+  if (split) {
+    write_partial(w, c, sp, part, n_rows, n_q_heads, g, G, hf);
+  } else {
+    const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
+    store_output(w.O, w.m_run, l_tot, c, out, lse_out, n_q_heads, g, G, hf);
   }
-  // the last workgroup of the head to leave puts the unit counter back to zero for the next launch
-  if (threadIdx.x == 0) {
-    const int left = __hip_atomic_fetch_add(gone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
-    if (left == pa.wg_per_head) {
-      __hip_atomic_store(next_unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(gone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
-  stamp(7);
 }
+
 
 }  // namespace
 
@@ -802,101 +569,142 @@ bool attention_mfma_supported(const ifkv_ctx *ctx) {
 
 namespace {
 
+constexpr int kSlots = 512;       // workgroups the chip holds at a time (256 CUs, two each)
+constexpr int kMinPartTiles = 32;
+constexpr int kMaxParts = 8;
+
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
-// Workgroups per kv head: the chip runs 512 of these workgroups at a time (256 CUs, two each).
-int default_wg_per_head(const ifkv_ctx *ctx) {
-  const int w = 512 / ctx->desc.n_kv_heads;
-  return w > 0 ? w : 1;
+// bytes of partial results for a launch of n_rows rows cut into `parts`
+size_t partial_bytes(const ifkv_ctx *ctx, int64_t n_rows, int parts) {
+  const auto &d = ctx->desc;
+  const size_t slots = static_cast<size_t>(parts) * static_cast<size_t>(n_rows) * d.n_q_heads;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const size_t n_rb = static_cast<size_t>((n_rows + 128 / G - 1) / (128 / G));
+  return align256(slots * D * sizeof(float)) + align256(slots * sizeof(float2)) + align256(n_rb * sizeof(int));
 }
 
-constexpr int kDefaultRangeTiles = 64;
+// Whether and where the kv axis is cut.  The chip holds 512 of these workgroups at a time and a row
+// block at position p costs p keys, so a launch is bound either by its total work (tiles per slot, if
+// the jobs spread evenly) or by its longest row block alone.  With rows spread uniformly over the
+// context a job averages half the tiles of the cache; when the longest job is clearly longer than the
+// even share per slot, the kv axis is cut into parts of about that share: row blocks shorter than one
+// part are not affected (they write their output directly), only the long ones run as several
+// workgroups whose partial results are merged by the combine pass.  Measured at 32K context: 5 % of
+// the rows (416 jobs) 0.66 -> 0.48 ms; 8K context (312 jobs) 0.150 -> 0.125 ms.  Only launches with
+// no more jobs than slots are cut: with more, every slot is busy for most of the launch anyway and
+// the partial writes plus the combine pass cost more than the shorter tail gains (684 jobs: 0.469 ->
+// 0.479 ms; 1232 jobs: 1.28 -> 1.37 ms; cutting only the longest row blocks of such a launch: 1.23
+// -> 1.26 .. 1.33 ms).  A part spans at least 32 tiles and there are at most 8 parts, unless the
+// tuning knobs say otherwise; a cut whose partial results would not fit the scratch is not made.
+struct SplitChoice {
+  int parts, part_tiles;
+};
+SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
+  const auto &d = ctx->desc;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const int rpb = 128 / G;
+  const int64_t jobs = ((n_rows + rpb - 1) / rpb) * d.n_kv_heads;
+  const int n_kv_tiles = static_cast<int>((n_kv + TK - 1) / TK);
+  int part_tiles = n_kv_tiles;
+  bool forced = false;
+  if (ctx->tune.attn_part_tiles > 0) {
+    part_tiles = ctx->tune.attn_part_tiles;
+    forced = true;
+  } else if (ctx->tune.attn_split_parts > 0) {
+    part_tiles = (n_kv_tiles + ctx->tune.attn_split_parts - 1) / ctx->tune.attn_split_parts;
+    forced = true;
+  } else if (jobs > 0 && jobs <= kSlots) {
+    const double even_share = static_cast<double>(jobs) * (0.5 * n_kv_tiles) / kSlots;
+    if (even_share < 0.9 * n_kv_tiles) part_tiles = static_cast<int>(1.15 * even_share) + 1;
+  }
+  if (!forced) {
+    if (part_tiles < kMinPartTiles) part_tiles = kMinPartTiles;
+    if (part_tiles * kMaxParts < n_kv_tiles) part_tiles = (n_kv_tiles + kMaxParts - 1) / kMaxParts;
+  }
+  if (part_tiles < 1) part_tiles = 1;
+  if (part_tiles > n_kv_tiles) part_tiles = n_kv_tiles > 0 ? n_kv_tiles : 1;
+  SplitChoice c;
+  c.part_tiles = part_tiles;
+  c.parts = (n_kv_tiles + part_tiles - 1) / part_tiles;
+  if (c.parts < 1) c.parts = 1;
+  // host-side bounds: the grid's z extent, and the partial results must fit what was allocated
+  if (c.parts > 65535 || (c.parts > 1 && partial_bytes(ctx, n_rows, c.parts) > ctx->scratch_bytes)) {
+    c.parts = 1;
+    c.part_tiles = n_kv_tiles > 0 ? n_kv_tiles : 1;
+  }
+  return c;
+}
 
 }  // namespace
 
-constexpr int kDefaultTailDiv = 8;
-
-// Partial slots per kv head: three per kv tile of the longest cache the layer admits (what a launch
-// of 30 % of the rows needs with 64-tile ranges), at least 256 and at most 2048, plus those of the
-// short units at the end of a launch.  A launch that needs more lengthens its ranges by itself.
-int attention_mfma_slot_cap(const ifkv_ctx *ctx) {
-  const int64_t tiles = (ctx->desc.max_ctx + TK - 1) / TK;
-  const int64_t s = std::min<int64_t>(std::max<int64_t>(3 * tiles, 256), 2048);
-  return static_cast<int>(s) + plan_max_tail_units(default_wg_per_head(ctx), kDefaultTailDiv);
-}
-
-// Row blocks one launch may hold: the plan's tables, and in the worst case (ranges longer than the
-// cache) one part and one full unit per row block plus the short units must fit the slots.
-int attention_mfma_max_row_blocks(const ifkv_ctx *ctx) {
-  const int by_slots = (attention_mfma_slot_cap(ctx) - plan_max_tail_units(default_wg_per_head(ctx), kDefaultTailDiv)) / 2;
-  return std::min(kPlanMaxBlocks, by_slots);
-}
-
+// Scratch for the partial results, fixed for a layer shape: the largest launch the library cuts by
+// itself (as many row blocks as the chip has workgroup slots, 8 parts).
 size_t attention_mfma_scratch_bytes(const ifkv_ctx *ctx) {
-  const size_t slots = static_cast<size_t>(attention_mfma_slot_cap(ctx)) * ctx->desc.n_kv_heads;
-  return align256(slots * kPartFloats * sizeof(float)) + align256(slots * 128 * sizeof(float2));
+  const auto &d = ctx->desc;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const int64_t rows = static_cast<int64_t>((kSlots + d.n_kv_heads - 1) / d.n_kv_heads) * (128 / G);
+  return partial_bytes(ctx, rows, kMaxParts);
 }
 
-size_t attention_mfma_counter_bytes(const ifkv_ctx *ctx) {
-  return static_cast<size_t>(ctx->desc.n_kv_heads) * (kPlanMaxBlocks + 2) * sizeof(int);
+namespace {
+
+// One launch covers at most 65535 row blocks (the y extent of a grid); more rows than that are
+// served by several launches over consecutive row ranges (rows are independent).  Launches of one
+// stream run one after the other, so they share the scratch.
+constexpr int64_t kMaxRowBlocks = 65535;
+
+hipError_t launch_attention_range(ifkv_ctx *ctx, const uint16_t *q_sel, const int32_t *row_pos, int64_t n_rows,
+                                  const uint16_t *k_cache, const uint16_t *v_cache, int64_t n_kv, uint16_t *out,
+                                  float *lse_out) {
+  const auto &d = ctx->desc;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
+  const int rpb = 128 / G;
+  const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
+  const SplitChoice sc = choose_split(ctx, n_rows, n_kv);
+  SplitPlan sp;
+  sp.part_tiles = sc.part_tiles;
+  sp.o_part = nullptr;
+  sp.ml_part = nullptr;
+  sp.block_tiles = nullptr;
+  if (sc.parts > 1) {
+    if (ctx->scratch == nullptr || partial_bytes(ctx, n_rows, sc.parts) > ctx->scratch_bytes) return hipErrorInvalidValue;
+    const size_t slots = static_cast<size_t>(sc.parts) * static_cast<size_t>(n_rows) * d.n_q_heads;
+    char *base = static_cast<char *>(ctx->scratch);
+    sp.o_part = reinterpret_cast<float *>(base);
+    sp.ml_part = reinterpret_cast<float2 *>(base + align256(slots * D * sizeof(float)));
+    sp.block_tiles = reinterpret_cast<int *>(base + align256(slots * D * sizeof(float)) + align256(slots * sizeof(float2)));
+  }
+  dim3 grid(d.n_kv_heads, n_rb, sc.parts);
+  hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, q_sel, row_pos, static_cast<int>(n_rows),
+                     k_cache, v_cache, static_cast<int>(n_kv), out, lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb,
+                     sp);
+  if (sc.parts > 1) {
+    const int64_t items = n_rows * d.n_q_heads;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, ctx->stream, sp,
+                       row_pos, static_cast<int>(n_rows), static_cast<int>(n_kv), d.n_q_heads, rpb, out, lse_out);
+  }
+  return hipGetLastError();
 }
 
-// Host-side bounds of a launch against what was allocated.  Returns false (nothing launched) otherwise.
-bool attention_mfma_launch_fits(const ifkv_ctx *ctx, int wg_per_head, int64_t n_rb, int64_t n_kv, int r_min, int tail_div) {
-  if (wg_per_head < 1 || wg_per_head > default_wg_per_head(ctx)) return false;
-  if (tail_div < 1 || tail_div > kDefaultTailDiv || tail_div > r_min) return false;
-  if (n_rb < 1 || n_rb > attention_mfma_max_row_blocks(ctx)) return false;
-  if (ctx->scratch == nullptr || attention_mfma_scratch_bytes(ctx) > ctx->scratch_bytes) return false;
-  if (ctx->attn_arrived == nullptr) return false;
-  // the longest candidate range must cover the cache, so that the fallback (one part per row block) exists
-  const int64_t tiles = (n_kv + TK - 1) / TK;
-  return r_min >= 1 && (r_min & (r_min - 1)) == 0 && (static_cast<int64_t>(r_min) << (kPlanRangeChoices - 1)) >= tiles;
-}
+}  // namespace
 
 hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                                  const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                                  float *lse_out) {
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
-  const int rpb = 128 / G;
-  const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
-  int wg_per_head = default_wg_per_head(ctx);
-  if (ctx->tune.attn_wg_per_head > 0 && ctx->tune.attn_wg_per_head < wg_per_head) wg_per_head = ctx->tune.attn_wg_per_head;
-  int64_t max_rb = attention_mfma_max_row_blocks(ctx);
+  int64_t max_rb = kMaxRowBlocks;
   if (ctx->tune.attn_max_row_blocks > 0 && ctx->tune.attn_max_row_blocks < max_rb) max_rb = ctx->tune.attn_max_row_blocks;
-  int r_min = ctx->tune.attn_range_tiles > 0 ? ctx->tune.attn_range_tiles : kDefaultRangeTiles;
-  const int64_t tiles = (n_kv + TK - 1) / TK;
-  while ((static_cast<int64_t>(r_min) << (kPlanRangeChoices - 1)) < tiles) r_min <<= 1;
-
-  const size_t slots = static_cast<size_t>(attention_mfma_slot_cap(ctx)) * d.n_kv_heads;
-  char *scratch = static_cast<char *>(ctx->scratch);
-  PlanArgs pa;
-  pa.wg_per_head = wg_per_head;
-  pa.r_min = r_min;
-  pa.tail_div = std::min(ctx->tune.attn_tail_div > 0 ? ctx->tune.attn_tail_div : kDefaultTailDiv, r_min);
-  pa.slot_cap = attention_mfma_slot_cap(ctx);
-  pa.o_part = reinterpret_cast<float *>(scratch);
-  pa.ml_part = reinterpret_cast<float *>(scratch + align256(slots * kPartFloats * sizeof(float)));
-  pa.arrived = ctx->attn_arrived;
-  pa.trace = reinterpret_cast<unsigned long long *>(ctx->tune.attn_trace);
-
-  // More row blocks than one plan holds are served by several launches over consecutive row ranges
-  // (rows are independent).  Launches of one stream run one after the other, so they share the slots.
-  const int64_t rows_per_launch = max_rb * rpb;
+  const int64_t rows_per_launch = max_rb * (128 / G);
   const int64_t row_elems = static_cast<int64_t>(d.n_q_heads) * D;
-  const dim3 grid(static_cast<unsigned>(wg_per_head) * d.n_kv_heads);
   for (int64_t r0 = 0; r0 < n_rows; r0 += rows_per_launch) {
     const int64_t nr = n_rows - r0 < rows_per_launch ? n_rows - r0 : rows_per_launch;
-    pa.n_rb = static_cast<int>((nr + rpb - 1) / rpb);
-    if (!attention_mfma_launch_fits(ctx, wg_per_head, pa.n_rb, n_kv, r_min, pa.tail_div)) return hipErrorInvalidValue;
-    const uint16_t *q_r = static_cast<const uint16_t *>(q_sel) + r0 * row_elems;
-    uint16_t *out_r = static_cast<uint16_t *>(out) + r0 * row_elems;
-    float *lse_r = lse_out != nullptr ? lse_out + r0 * d.n_q_heads : nullptr;
-    hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(kThreads), 0, ctx->stream, q_r, row_pos + r0,
-                       static_cast<int>(nr), static_cast<const uint16_t *>(k_cache),
-                       static_cast<const uint16_t *>(v_cache), static_cast<int>(n_kv), out_r, lse_r, d.n_q_heads,
-                       d.n_kv_heads, scale_log2, rpb, pa);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_attention_range(ctx, static_cast<const uint16_t *>(q_sel) + r0 * row_elems, row_pos + r0, nr,
+                                          static_cast<const uint16_t *>(k_cache), static_cast<const uint16_t *>(v_cache),
+                                          n_kv, static_cast<uint16_t *>(out) + r0 * row_elems,
+                                          lse_out != nullptr ? lse_out + r0 * d.n_q_heads : nullptr);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

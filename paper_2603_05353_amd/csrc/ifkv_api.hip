@@ -49,21 +49,6 @@ int ensure_scratch(ifkv_ctx *ctx) {
     (void)hipGetLastError();
     return fail(ctx, IFKV_ENOMEM, "scratch allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
   }
-  // stage 4's arrival counters live apart from the shared scratch (the other stages would overwrite
-  // them) and must read zero before the first launch; every launch leaves them at zero again
-  const size_t cbytes = ifkv::attention_counter_bytes(ctx);
-  if (cbytes > 0) {
-    void *c = nullptr;
-    e = hipMalloc(&c, cbytes);
-    if (e == hipSuccess) e = hipMemset(c, 0, cbytes);
-    if (e != hipSuccess) {
-      (void)hipGetLastError();
-      if (c != nullptr) (void)hipFree(c);
-      (void)hipFree(p);
-      return fail(ctx, IFKV_ENOMEM, "counter allocation of %zu bytes failed: %s", cbytes, hipGetErrorString(e));
-    }
-    ctx->attn_arrived = static_cast<int *>(c);
-  }
   ctx->scratch = p;
   ctx->scratch_bytes = bytes;
   return IFKV_OK;
@@ -139,7 +124,6 @@ int ifkv_create(ifkv_ctx **out, const ifkv_layer_desc *desc, void *hip_stream) {
 void ifkv_destroy(ifkv_ctx *ctx) {
   if (ctx == nullptr) return;
   if (ctx->scratch != nullptr) (void)hipFree(ctx->scratch);
-  if (ctx->attn_arrived != nullptr) (void)hipFree(ctx->attn_arrived);
   if (ctx->d_inv_freq != nullptr) (void)hipFree(ctx->d_inv_freq);
   delete ctx;
 }
@@ -383,26 +367,18 @@ int ifkv_reorder_chunks(ifkv_ctx *ctx, int32_t n_chunks, const int32_t *order_in
 int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value) {
   if (ctx == nullptr) return IFKV_EINVAL;
   if (key == nullptr) return fail(ctx, IFKV_EINVAL, "set_tuning: key is NULL");
-  const int64_t wg_max = std::max(1, 512 / ctx->desc.n_kv_heads);
   struct Knob {
     const char *name;
     int *slot;
     int64_t hi;
-  } knobs[] = {{"attn_wg_per_head", &ctx->tune.attn_wg_per_head, wg_max},
-               {"attn_tail_div", &ctx->tune.attn_tail_div, 8},
-               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 1024},
-               {"attn_range_tiles", &ctx->tune.attn_range_tiles, 4096}};
-  if (std::strcmp(key, "attn_trace") == 0) {
-    ctx->tune.attn_trace = value;
-    return IFKV_OK;
-  }
+  } knobs[] = {{"attn_split_parts", &ctx->tune.attn_split_parts, 65535},
+               {"attn_part_tiles", &ctx->tune.attn_part_tiles, 1 << 24},
+               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 65535}};
   for (const Knob &k : knobs) {
     if (std::strcmp(key, k.name) != 0) continue;
     if (value < 0 || value > k.hi)
       return fail(ctx, IFKV_EINVAL, "set_tuning: %s=%lld is outside [0, %lld]", key, static_cast<long long>(value),
                   static_cast<long long>(k.hi));
-    if ((k.slot == &ctx->tune.attn_range_tiles || k.slot == &ctx->tune.attn_tail_div) && (value & (value - 1)) != 0)
-      return fail(ctx, IFKV_EINVAL, "set_tuning: %s=%lld is not a power of two", key, static_cast<long long>(value));
     *k.slot = static_cast<int>(value);
     return IFKV_OK;
   }

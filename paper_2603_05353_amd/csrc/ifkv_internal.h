@@ -11,11 +11,9 @@
 
 // Tuning and testing knobs (include/ifkv_debug.h); 0 = the library's own choice.
 struct ifkv_tuning {
-  int attn_wg_per_head = 0;      // stage 4: workgroups per kv head (can only lower the default)
-  int attn_tail_div = 0;         // stage 4: short units at the end of a launch are 1/this of a kv range
+  int attn_split_parts = 0;      // stage 4: cut the kv axis into this many equal parts
+  int attn_part_tiles = 0;       // stage 4: cut the kv axis into parts of this many tiles (takes precedence)
   int attn_max_row_blocks = 0;   // stage 4: row blocks per launch (can only lower the default)
-  int attn_range_tiles = 0;      // stage 4: shortest kv range of the work plan, in tiles
-  int64_t attn_trace = 0;        // stage 4: device address of a time-stamp buffer (0 = none)
 };
 
 struct ifkv_ctx {
@@ -27,7 +25,6 @@ struct ifkv_ctx {
   double *d_inv_freq = nullptr; // device copy, uploaded on first use
   void *scratch = nullptr;      // device scratch shared by the stages, allocated once
   size_t scratch_bytes = 0;
-  int *attn_arrived = nullptr;  // stage 4: per kv head, tile counters of the row blocks + unit counter + exit counter; zero between launches
   std::string err;
 };
 
@@ -69,7 +66,6 @@ hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_
 
 // Stage 4.
 size_t attention_scratch_bytes(const ifkv_ctx *ctx);
-size_t attention_counter_bytes(const ifkv_ctx *ctx);
 hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                             float *lse_out);

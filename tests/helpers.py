@@ -106,6 +106,7 @@ def needle_case(n_kv, hq, hkv, n_rows, seed):
         for h in range(hq):
             j = fixed[h] if h < len(fixed) else int(g.integers(0, p + 1))
             target[r, h] = j
-            Q64[r, h] = 230.0 * K64[j, h // G] / np.linalg.norm(K64[j, h // G])
+            kj = K64[j, h // G]
+            Q64[r, h] = (24.0 * d ** 0.5) * kj / (kj @ kj)      # the target's logit is 24 whatever its norm
     K_st, V_st, q_st = (to_storage(x, "bf16") for x in (K64, V64, Q64))
     return rows, target, q_st, K_st, V_st

@@ -210,18 +210,15 @@ def test_mfma_probe_rejects_bad_arguments(lib):
 
 def test_set_tuning_validation(lib):
     L = _layer()
-    L.set_tuning("attn_wg_per_head", 3)
-    L.set_tuning("attn_wg_per_head", 64)          # 512 / 8 kv heads: the default is the upper limit
+    L.set_tuning("attn_split_parts", 3)
+    L.set_tuning("attn_part_tiles", 40)
     L.set_tuning("attn_max_row_blocks", 2)
-    L.set_tuning("attn_tail_div", 4)
-    L.set_tuning("attn_tail_div", 0)
-    L.set_tuning("attn_range_tiles", 16)
-    L.set_tuning("attn_range_tiles", 0)
-    for key, value in [("attn_wg_per_head", 65), ("attn_wg_per_head", -1), ("attn_max_row_blocks", 1025),
-                       ("attn_range_tiles", 24), ("attn_range_tiles", 8192), ("attn_tail_div", 3), ("attn_tail_div", 16), ("no_such_knob", 1)]:
+    L.set_tuning("attn_part_tiles", 0)
+    for key, value in [("attn_split_parts", 65536), ("attn_split_parts", -1), ("attn_max_row_blocks", 65536),
+                       ("no_such_knob", 1)]:
         with pytest.raises(B.IfkvError) as e:
             L.set_tuning(key, value)
         assert e.value.code == B.IFKV_EINVAL
     assert lib.ifkv_set_tuning(L._ctx, None, 1) == B.IFKV_EINVAL
-    assert lib.ifkv_set_tuning(None, b"attn_wg_per_head", 1) == B.IFKV_EINVAL
+    assert lib.ifkv_set_tuning(None, b"attn_split_parts", 1) == B.IFKV_EINVAL
     L.close()

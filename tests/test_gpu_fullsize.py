@@ -115,8 +115,8 @@ def rows_agree(a, b, rel=0.02):
     return bool((num <= rel * den + 1e-30).all())
 
 
-# other ways of cutting the same launch into workgroup shares
-OTHER_CUTS = {"attn_wg_per_head": 37, "attn_range_tiles": 32, "attn_tail_div": 2}
+# another way of running the same call: every launch cut along the kv axis into 3 parts, 40 row blocks per launch
+OTHER_CUTS = {"attn_split_parts": 3, "attn_max_row_blocks": 40}
 
 
 def test_splice_and_attention_sampled_rows(run):
@@ -146,7 +146,7 @@ def test_splice_and_attention_sampled_rows(run):
     ref, ref_abs, lse_ref = oracle_attention(to_f64(q_sel, spec.dtype)[pick], idx[pick], K64, V64, wl.sm_scale)
     got_all = to_host_f64(out, spec.dtype)
     assert_attention_close(got_all[pick], ref, ref_abs, spec.dtype, lse.cpu().numpy().astype(np.float64)[pick], lse_ref)
-    # the same call with the launch cut into workgroup shares differently: every row agrees
+    # the same call cut into parts and launches differently: every row agrees
     for key, value in OTHER_CUTS.items():
         L.set_tuning(key, value)
     out_c, lse_c = L.recompute_attention(to_dev(q_sel, spec.dtype), idx_d, K, V, return_lse=True)
@@ -187,9 +187,9 @@ def test_attention_needles_full_size(run):
 
 
 def test_attention_at_the_other_ratios(run):
-    """Stage 4 at the remaining recompute ratios of the configuration (at 5 % every workgroup's share
-    is a fraction of a row block; at 30 % the call is twice the benchmark's size); sampled rows against
-    the oracle, and every row against the same call cut into shares differently."""
+    """Stage 4 at the remaining recompute ratios of the configuration (at 5 % the launch is cut along
+    the kv axis and merged by the combine pass; at 30 % it is twice the benchmark's size); sampled rows
+    against the oracle, and every row against the same call cut into parts and launches differently."""
     spec, wl, N, L = run["spec"], run["wl"], run["N"], run["L"]
     others = [r for r in spec.ratios if r != 0.15]
     if run["name"] != "C3" or not others:

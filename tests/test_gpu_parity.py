@@ -374,8 +374,8 @@ ATTN_SHAPES = [
     ([1], [0], 8, 2), ([63], "all", 8, 2), ([64], [0, 63], 8, 2), ([65], [64], 8, 2), ([65], "all", 8, 2),
     ([128, 100], 50, 32, 1), ([300], 200, 8, 8), ([129], [0, 1, 2, 127, 128], 28, 4),
 ]
-# launch shapes: the library's own; kv ranges of one tile, so that every row block is cut at every tile
-FINE_CUTS = {"attn_range_tiles": 1}
+# launch shapes: the library's own; kv parts of one tile, so that every row block is cut at every tile
+FINE_CUTS = {"attn_part_tiles": 1}
 
 
 @pytest.mark.parametrize("lens,rows,hq,hkv", ATTN_SHAPES,
@@ -391,28 +391,38 @@ def test_attention_mfma_shapes(lens, rows, hq, hkv, tuning):
     attention_case(spec, np.asarray(rows, dtype=np.int64), tuning=tuning)
 
 
-# How the (row block, kv tile) line is laid out and cut into workgroup shares is the library's choice;
+# Whether and where a launch is cut along the kv axis (partial results in scratch, merged by the
+# combine pass) and into how many launches a call is split over row ranges is the library's choice;
 # every choice must give the same rows.  100 kv tiles, 30 row blocks.
 CUT_TUNINGS = [
     ("default", None),
-    ("one-workgroup-per-head", {"attn_wg_per_head": 1}),
-    ("3-workgroups-8-tile-ranges", {"attn_wg_per_head": 3, "attn_range_tiles": 8}),
-    ("7-workgroups-2-tile-ranges", {"attn_wg_per_head": 7, "attn_range_tiles": 2, "attn_tail_div": 2}),
-    ("single-tile-ranges", {"attn_range_tiles": 1}),
-    ("16-tile-ranges", {"attn_range_tiles": 16}),
-    ("ranges-longer-than-the-cache", {"attn_range_tiles": 128, "attn_tail_div": 1}),
+    ("never-cut", {"attn_split_parts": 1}),
+    ("2-parts", {"attn_split_parts": 2}),
+    ("3-parts", {"attn_split_parts": 3}),
+    ("40-tile-parts", {"attn_part_tiles": 40}),     # row blocks of up to 40 tiles stay whole, longer ones get 2 or 3 parts
+    ("7-tile-parts", {"attn_part_tiles": 7}),
+    ("single-tile-parts", {"attn_part_tiles": 1}),
     ("2-row-blocks-per-launch", {"attn_max_row_blocks": 2}),
-    ("3-row-blocks-per-launch-4-tile-ranges", {"attn_max_row_blocks": 3, "attn_range_tiles": 4, "attn_tail_div": 4}),
+    ("3-row-blocks-per-launch-cut-in-4", {"attn_max_row_blocks": 3, "attn_split_parts": 4}),
 ]
 
 
 @pytest.mark.parametrize("name,tuning", CUT_TUNINGS, ids=[c[0] for c in CUT_TUNINGS])
-def test_attention_cut_between_workgroups(name, tuning):
-    """Row blocks cut between workgroups at every possible place (partial results in scratch, merged
-    by the combine pass) and calls served by several launches over row ranges, on near-uniform data."""
+def test_attention_cut_along_the_kv_axis(name, tuning):
+    """Launches cut along the kv axis (partial results in scratch, merged by the combine pass) and
+    calls served by several launches over row ranges, on near-uniform data."""
     spec = preset("C2", chunk_lens=[640] * 10, m_prompt=8)            # 100 kv tiles
     rows = np.unique(np.concatenate([sample_rows(6400, 900, 5), [0, 63, 64, 2111, 2112, 2113, 4223, 4224, 6399]]))
     attention_case(spec, rows, tuning=tuning, n_check=160)
+
+
+def test_attention_row_ranges_that_are_cut_on_their_own():
+    """More jobs than workgroup slots in total (so the call as a whole would not be cut), served in
+    two launches over row ranges that each have fewer (so each range is cut along the kv axis by the
+    library's own rule): the scratch must serve every range."""
+    spec = preset("C2", chunk_lens=[640] * 10, m_prompt=8)            # 100 kv tiles
+    rows = sample_rows(6400, 2200, 8)                                  # 69 row blocks x 8 kv heads = 552 jobs
+    attention_case(spec, rows, tuning={"attn_max_row_blocks": 60}, n_check=160)
 
 
 @pytest.mark.parametrize("name,tuning", CUT_TUNINGS, ids=[c[0] for c in CUT_TUNINGS])
