@@ -196,6 +196,24 @@ int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx,
                      int32_t *idx_out, int64_t *k_out);
 
 /*
+ * ifkv_select_topk for callers that cannot allocate device memory: code under
+ * HIP graph capture before the context's scratch exists, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same result bit for bit.
+ * The call allocates nothing on host or device: the histograms and counts its
+ * kernels need live in a static device array inside the library
+ * (24 KiB + 8 bytes per 4096 scores, 32 KiB in all; every GPU the library runs
+ * on holds it until the process ends), which limits n_ctx to 2^22 = 4194304.
+ * All calls on one GPU share that array, whatever their context: calls that
+ * overlap on one GPU (different streams) race; calls on one stream do not.
+ * What must start at zero is cleared by a kernel of the call itself.
+ *
+ * Errors: as ifkv_select_topk, and IFKV_ESHAPE for n_ctx above the limit.
+ */
+int ifkv_select_topk_noalloc(ifkv_ctx *ctx, const float *scores, int64_t n_ctx,
+                             double ratio, int64_t k_override, int32_t *idx_out,
+                             int64_t *k_out);
+
+/*
  * Stage 4 -- "KV Recomputation" paragraph: every selected token runs an
  * ordinary causal forward pass at its global position over the concatenated
  * sequence.  This call is the attention of that pass.

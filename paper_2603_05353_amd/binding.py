@@ -24,7 +24,7 @@ IFKV_FLAG_FORCE_GENERIC = 1
 
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
-    "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk",
+    "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk", "ifkv_select_topk_noalloc",
     "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
     "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",   # include/ifkv_calibrate.h
     "ifkv_set_tuning",                                                       # include/ifkv_debug.h
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.ifkv_score_tokens.restype = C.c_int
     lib.ifkv_select_topk.argtypes = [vp, vp, i64, C.c_double, i64, vp, C.POINTER(i64)]
     lib.ifkv_select_topk.restype = C.c_int
+    lib.ifkv_select_topk_noalloc.argtypes = [vp, vp, i64, C.c_double, i64, vp, C.POINTER(i64)]
+    lib.ifkv_select_topk_noalloc.restype = C.c_int
     lib.ifkv_recompute_attention.argtypes = [vp, vp, vp, i64, vp, vp, i64, vp, vp]
     lib.ifkv_recompute_attention.restype = C.c_int
     lib.ifkv_splice_kv.argtypes = [vp, vp, vp, vp, i64, vp, vp, i64]
@@ -211,6 +213,13 @@ class Layer:
         k_out = C.c_int64()
         self._check(self._lib.ifkv_select_topk(self._ctx, _ptr(scores), n_ctx, float(ratio), int(k),
                                                _ptr(idx_out), C.byref(k_out)))
+        return idx_out[: int(k_out.value)]
+
+    def select_topk_noalloc(self, scores: torch.Tensor, idx_out: torch.Tensor, ratio: float = 0.0, k: int = -1) -> torch.Tensor:
+        """ifkv_select_topk_noalloc: the caller brings idx_out; the call allocates nothing."""
+        k_out = C.c_int64()
+        self._check(self._lib.ifkv_select_topk_noalloc(self._ctx, _ptr(scores), int(scores.shape[0]), float(ratio), int(k),
+                                                       _ptr(idx_out), C.byref(k_out)))
         return idx_out[: int(k_out.value)]
 
     def recompute_attention(self, q_sel: torch.Tensor, row_pos: torch.Tensor, k_cache: torch.Tensor,

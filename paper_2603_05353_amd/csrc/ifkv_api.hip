@@ -230,29 +230,59 @@ int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const 
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "score kernel launch");
 }
 
-int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double ratio, int64_t k_override,
-                     int32_t *idx_out, int64_t *k_out) {
-  if (ctx == nullptr) return IFKV_EINVAL;
+namespace {
+
+// Argument checks and the budget shared by the two top-k entry points.  Returns IFKV_OK with *k set.
+int topk_budget(ifkv_ctx *ctx, int64_t n_ctx, double ratio, int64_t k_override, int64_t *k) {
   if (n_ctx < 0) return fail(ctx, IFKV_EINVAL, "select_topk: n_ctx is negative");
   if (n_ctx > ctx->desc.max_ctx || n_ctx >= (int64_t(1) << 31))
     return fail(ctx, IFKV_ESHAPE, "select_topk: n_ctx=%lld exceeds max_ctx", static_cast<long long>(n_ctx));
-  int64_t k;
   if (k_override >= 0) {
-    k = k_override;
+    *k = k_override;
   } else {
     if (!(ratio >= 0.0 && ratio <= 1.0))
       return fail(ctx, IFKV_EINVAL, "select_topk: ratio=%g is outside [0, 1]", ratio);
-    k = static_cast<int64_t>(std::floor(ratio * static_cast<double>(n_ctx)));  // k = floor(rho N)
+    *k = static_cast<int64_t>(std::floor(ratio * static_cast<double>(n_ctx)));  // k = floor(rho N)
   }
-  if (k > n_ctx)
-    return fail(ctx, IFKV_EINVAL, "select_topk: k=%lld exceeds n_ctx=%lld", static_cast<long long>(k),
+  if (*k > n_ctx)
+    return fail(ctx, IFKV_EINVAL, "select_topk: k=%lld exceeds n_ctx=%lld", static_cast<long long>(*k),
                 static_cast<long long>(n_ctx));
+  return IFKV_OK;
+}
+
+}  // namespace
+
+int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double ratio, int64_t k_override,
+                     int32_t *idx_out, int64_t *k_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  int64_t k = 0;
+  int rc = topk_budget(ctx, n_ctx, ratio, k_override, &k);
+  if (rc != IFKV_OK) return rc;
   if (k_out != nullptr) *k_out = k;
   if (k == 0) return IFKV_OK;
   if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk: NULL pointer");
-  int rc = ensure_scratch(ctx);
+  rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
-  hipError_t e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out);
+  hipError_t e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out, ctx->scratch);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "top-k kernel launch");
+}
+
+int ifkv_select_topk_noalloc(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double ratio, int64_t k_override,
+                             int32_t *idx_out, int64_t *k_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  int64_t k = 0;
+  int rc = topk_budget(ctx, n_ctx, ratio, k_override, &k);
+  if (rc != IFKV_OK) return rc;
+  if (n_ctx > ifkv::topk_static_max_ctx())
+    return fail(ctx, IFKV_ESHAPE, "select_topk_noalloc: n_ctx=%lld exceeds the %lld scores this entry point serves",
+                static_cast<long long>(n_ctx), static_cast<long long>(ifkv::topk_static_max_ctx()));
+  if (k_out != nullptr) *k_out = k;
+  if (k == 0) return IFKV_OK;
+  if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk_noalloc: NULL pointer");
+  void *work = nullptr;
+  hipError_t e = ifkv::topk_static_scratch(&work);
+  if (e != hipSuccess) return hip_fail(ctx, e, "address of the static scratch");
+  e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out, work);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "top-k kernel launch");
 }
 

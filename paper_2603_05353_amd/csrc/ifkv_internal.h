@@ -62,7 +62,10 @@ hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, cons
 
 // Stage 3.
 size_t topk_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx);
-hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out);
+hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out, void *work);
+// the entry point that allocates nothing: its static device scratch and the largest n_ctx it serves
+hipError_t topk_static_scratch(void **out);
+int64_t topk_static_max_ctx();
 
 // Stage 4.
 size_t attention_scratch_bytes(const ifkv_ctx *ctx);

@@ -15,6 +15,8 @@
 //
 // Vectors of more than 32768 scores do not fit one workgroup's registers; they take the
 // multi-workgroup radix select further down (six short launches).
+#include <mutex>
+
 #include "ifkv_device.h"
 #include "ifkv_internal.h"
 
@@ -479,13 +481,52 @@ hipError_t launch_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, con
   return hipGetLastError();
 }
 
+namespace {
+
+constexpr size_t kSelStateBytes = (sizeof(SelectState) + 255) & ~static_cast<size_t>(255);
+
+// Device memory of the entry point that allocates nothing: the histograms and the per-workgroup
+// counts of the largest score vector it accepts.  Every GPU the library runs on holds its own copy
+// of the array at its own address; in host code the array's name is only a handle for looking that
+// address up, never a pointer to pass on.
+constexpr int64_t kStaticMaxCtx = int64_t(1) << 22;
+constexpr size_t kStaticScratchBytes = kSelStateBytes + static_cast<size_t>(kStaticMaxCtx / kSelChunk) * sizeof(uint2);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void *g_static_ptr[kMaxDevices] = {};
+
+}  // namespace
+
+int64_t topk_static_max_ctx() { return kStaticMaxCtx; }
+
+// Address of the static scratch on the device that is current; looked up once per device.
+hipError_t topk_static_scratch(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static_ptr[dev] == nullptr) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+
 size_t topk_scratch_bytes(const ifkv_ctx *, int64_t n_ctx) {
   if (n_ctx <= 1024 * 32) return 0;
   const size_t blocks = static_cast<size_t>((n_ctx + kSelChunk - 1) / kSelChunk);
-  return ((sizeof(SelectState) + 255) & ~static_cast<size_t>(255)) + blocks * sizeof(uint2);
+  return kSelStateBytes + blocks * sizeof(uint2);
 }
 
-hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out) {
+// `work`: device memory of at least topk_scratch_bytes(n_ctx) bytes (may be null when that is 0)
+hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_t k, int32_t *idx_out, void *work) {
   if (k <= 0 || n_ctx <= 0) return hipSuccess;
   const int n = static_cast<int>(n_ctx);
   const int kk = static_cast<int>(k);
@@ -495,9 +536,9 @@ hipError_t launch_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, int64_
   } else if (n <= 1024 * 32) {
     hipLaunchKernelGGL((topk_resident_kernel<1024, 1>), dim3(1), dim3(1024), 0, st, scores, n, kk, idx_out);
   } else {
-    SelectState *state = static_cast<SelectState *>(ctx->scratch);
-    uint2 *counts = reinterpret_cast<uint2 *>(static_cast<char *>(ctx->scratch) +
-                                              ((sizeof(SelectState) + 255) & ~static_cast<size_t>(255)));
+    if (work == nullptr) return hipErrorInvalidValue;
+    SelectState *state = static_cast<SelectState *>(work);
+    uint2 *counts = reinterpret_cast<uint2 *>(static_cast<char *>(work) + kSelStateBytes);
     const unsigned blocks = static_cast<unsigned>((n + kSelChunk - 1) / kSelChunk);
     hipLaunchKernelGGL(select_zero_kernel, dim3(6), dim3(1024), 0, st, state);
     for (int pass = 0; pass < 3; ++pass)
