@@ -108,7 +108,7 @@ def main():
     K = torch.empty(N, spec.n_kv_heads, spec.head_dim, dtype=tdt, device=dev)
     V = torch.empty_like(K)
     scores = torch.empty(N, dtype=torch.float32, device=dev)
-    k_sel = int(np.floor(ratio * N))
+    k_sel = L.budget_of(N, ratio)     # k = floor(ratio N) as the library evaluates it (host only)
     idx = torch.empty(max(k_sel, 1), dtype=torch.int32, device=dev)
 
     # one untimed pass to learn the selected set, then build the recompute rows for it

@@ -39,7 +39,11 @@
  * - Preconditions on device-resident data that cannot be checked without a
  *   host sync (row_pos strictly ascending, idx unique) are the caller's
  *   responsibility; indices outside [0, n_kv) are skipped by the kernels, never
- *   dereferenced.
+ *   dereferenced.  A context created with IFKV_FLAG_VALIDATE checks both on
+ *   the device before the stage runs, at the price of a host sync per call.
+ * - Tensor layouts: chunk caches, queries, outputs and freshly projected rows
+ *   are packed row-major as stated per argument; the concatenated caches
+ *   follow the descriptor's token_stride / head_stride.
  * - A context is not thread-safe; use one per host thread / stream.
  */
 #ifndef IFKV_H
@@ -72,6 +76,13 @@ typedef enum { IFKV_ROPE_HALF = 0, IFKV_ROPE_INTERLEAVED = 1 } ifkv_rope_pairing
 /* Route every stage through the plain fp32 ALU kernels even where a bf16 MFMA
  * kernel exists (cross-checking and debugging). */
 #define IFKV_FLAG_FORCE_GENERIC 1u
+/* Debug mode: check on the device the preconditions that host code cannot see
+ * -- row_pos of ifkv_recompute_attention strictly ascending, idx of
+ * ifkv_splice_kv free of duplicates -- before the stage runs.  With this flag
+ * the two calls wait for the stream (the answer has to reach the host) and
+ * return IFKV_EINVAL, with the offending position in the message, instead of
+ * computing on bad input.  Without it such input is undefined behaviour. */
+#define IFKV_FLAG_VALIDATE 2u
 
 typedef struct {
   int32_t dtype;      /* ifkv_dtype of K, V, Q and attention outputs */
@@ -85,6 +96,18 @@ typedef struct {
   int64_t max_ctx;    /* largest number of cache rows (context + prompt rows) any call will pass */
   int32_t max_prompt; /* largest m_prompt */
   uint32_t flags;     /* IFKV_FLAG_* */
+  /* Layout of the concatenated caches (k_out / v_out of stage 1, k_global of
+   * stage 2, k_cache / v_cache of stages 4 and 5), in elements: element c of kv
+   * head h of cache row t sits at t * token_stride + h * head_stride + c.  Both
+   * 0 selects the packed [T, H_kv, d] layout (token_stride = H_kv * d,
+   * head_stride = d).  [H_kv, T_cap, d] is token_stride = d, head_stride =
+   * T_cap * d.  Both must be multiples of 16 bytes' worth of elements, at least
+   * d, and the heads of a row / the rows of a head must not overlap: either
+   * token_stride >= (H_kv - 1) * head_stride + d or head_stride >= (max_ctx - 1)
+   * * token_stride + d.  Chunk caches, query tensors and freshly projected rows
+   * (k_new, v_new, k_prompt, x of ifkv_rope_rows) are always packed. */
+  int64_t token_stride;
+  int64_t head_stride;
 } ifkv_layer_desc;
 
 /* Creates a context for one layer shape bound to `hip_stream` (a hipStream_t;
@@ -185,7 +208,8 @@ int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx,
  *   ratio       rho in [0, 1]; used when k_override < 0: k = floor(ratio * n_ctx)
  *               evaluated in double precision
  *   k_override  >= 0: use this k (must be <= n_ctx)
- *   idx_out     device int32 [k]
+ *   idx_out     device int32 [k]; NULL: nothing is selected, the call only
+ *               reports k (to size idx_out for a second call), no GPU work
  *   k_out       host: k (known without a device sync); may be NULL
  *
  * Errors: IFKV_EINVAL (ratio outside [0,1], k > n_ctx, NULL pointers),

@@ -2,6 +2,7 @@
 C ABI, see include/ifkv.h).  The shared library is loaded on first use."""
 from .binding import (  # noqa: F401
     IFKV_FLAG_FORCE_GENERIC,
+    IFKV_FLAG_VALIDATE,
     IfkvError,
     Layer,
     LIB_PATH,

@@ -21,6 +21,7 @@ IFKV_OK, IFKV_EINVAL, IFKV_ESHAPE, IFKV_EDTYPE, IFKV_ENOMEM, IFKV_EHIP = 0, -1, 
 IFKV_F32, IFKV_BF16 = 0, 1
 IFKV_ROPE_HALF, IFKV_ROPE_INTERLEAVED = 0, 1
 IFKV_FLAG_FORCE_GENERIC = 1
+IFKV_FLAG_VALIDATE = 2
 
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
@@ -37,6 +38,7 @@ class LayerDesc(C.Structure):
         ("head_dim", C.c_int32), ("rope_theta", C.c_double), ("inv_freq", C.POINTER(C.c_double)),
         ("pairing", C.c_int32), ("sm_scale", C.c_float), ("max_ctx", C.c_int64),
         ("max_prompt", C.c_int32), ("flags", C.c_uint32),
+        ("token_stride", C.c_int64), ("head_stride", C.c_int64),
     ]
 
 
@@ -126,7 +128,8 @@ class Layer:
     def __init__(self, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float,
                  max_ctx: int, max_prompt: int, pairing: str = "half", sm_scale: float = 0.0,
                  inv_freq: Optional[Sequence[float]] = None, flags: int = 0,
-                 stream: Optional[int] = None, device: str = "cuda:0"):
+                 stream: Optional[int] = None, device: str = "cuda:0",
+                 token_stride: int = 0, head_stride: int = 0):
         self._lib = load_library()
         self.dtype = dtype
         self.torch_dtype = _TORCH_DTYPE[dtype]
@@ -143,6 +146,10 @@ class Layer:
         desc.pairing = IFKV_ROPE_HALF if pairing == "half" else IFKV_ROPE_INTERLEAVED
         desc.sm_scale = float(sm_scale)
         desc.max_ctx, desc.max_prompt, desc.flags = int(max_ctx), int(max_prompt), int(flags)
+        desc.token_stride, desc.head_stride = int(token_stride), int(head_stride)
+        self.token_stride = int(token_stride) or n_kv_heads * head_dim
+        self.head_stride = int(head_stride) or head_dim
+        self.max_ctx = int(max_ctx)
         if stream is None and torch.cuda.is_available():
             stream = torch.cuda.current_stream().cuda_stream
         self._ctx = C.c_void_p()
@@ -169,6 +176,36 @@ class Layer:
     def _empty(self, *shape, dtype=None):
         return torch.empty(*shape, dtype=dtype or self.torch_dtype, device=self.device)
 
+    def empty_cache(self, n_rows: int) -> torch.Tensor:
+        """A concatenated cache [n_rows, H_kv, d] in the layout the layer was created with."""
+        return torch.empty_strided((int(n_rows), self.n_kv_heads, self.head_dim), (self.token_stride, self.head_stride, 1),
+                                   dtype=self.torch_dtype, device=self.device)
+
+    # Argument marshalling: a pointer is only taken from a tensor that is what the C call expects
+    # (device, dtype, shape, layout); anything else would be read as garbage or out of bounds.
+    def _packed(self, t: Optional[torch.Tensor], name: str, tail: Tuple[int, ...], dtype=None, rows: Optional[int] = None):
+        if t is None:
+            return None
+        want = dtype or self.torch_dtype
+        if not t.is_cuda or t.dtype != want:
+            raise ValueError(f"{name}: expected a {want} tensor on the GPU, got {t.dtype} on {t.device}")
+        if tuple(t.shape[1:]) != tuple(tail) or (rows is not None and t.shape[0] < rows):
+            raise ValueError(f"{name}: expected shape [{'R' if rows is None else rows}, {', '.join(map(str, tail))}], got {tuple(t.shape)}")
+        if not t.is_contiguous():
+            raise ValueError(f"{name}: must be contiguous")
+        return t.data_ptr()
+
+    def _cache(self, t: Optional[torch.Tensor], name: str):
+        if t is None:
+            return None
+        if not t.is_cuda or t.dtype != self.torch_dtype:
+            raise ValueError(f"{name}: expected a {self.torch_dtype} tensor on the GPU, got {t.dtype} on {t.device}")
+        if t.dim() != 3 or tuple(t.shape[1:]) != (self.n_kv_heads, self.head_dim):
+            raise ValueError(f"{name}: expected shape [T, {self.n_kv_heads}, {self.head_dim}], got {tuple(t.shape)}")
+        if t.shape[0] > 1 and tuple(t.stride()) != (self.token_stride, self.head_stride, 1):
+            raise ValueError(f"{name}: strides {tuple(t.stride())} are not the layer's ({self.token_stride}, {self.head_stride}, 1)")
+        return t.data_ptr()
+
     # -- the five stages ------------------------------------------------------
     def reposition_keys(self, k_chunks: List[torch.Tensor], v_chunks: Optional[List[torch.Tensor]] = None,
                         chunk_order: Optional[Sequence[int]] = None,
@@ -180,18 +217,23 @@ class Layer:
         lens = [int(t.shape[0]) for t in k_chunks]
         N = sum(lens)
         if k_out is None:
-            k_out = self._empty(N, self.n_kv_heads, self.head_dim)
+            k_out = self.empty_cache(N)
         if v_chunks is not None and v_out is None:
-            v_out = self._empty(N, self.n_kv_heads, self.head_dim)
-        kp = (C.c_void_p * n)(*[t.data_ptr() if t.shape[0] else None for t in k_chunks])
+            v_out = self.empty_cache(N)
+        kv_tail = (self.n_kv_heads, self.head_dim)
+        kp = (C.c_void_p * n)(*[self._packed(t, "k_chunks[i]", kv_tail) if t.shape[0] else None for t in k_chunks])
         vp = None
         if v_chunks is not None:
-            vp = (C.c_void_p * n)(*[t.data_ptr() if t.shape[0] else None for t in v_chunks])
+            if [int(t.shape[0]) for t in v_chunks] != lens:
+                raise ValueError("v_chunks: lengths differ from k_chunks")
+            vp = (C.c_void_p * n)(*[self._packed(t, "v_chunks[i]", kv_tail) if t.shape[0] else None for t in v_chunks])
+        if k_out.shape[0] < N or (v_out is not None and v_out.shape[0] < N):
+            raise ValueError("k_out / v_out: fewer rows than the chunks hold")
         starts = (C.c_int64 * max(n, 1))()
         n_ctx = C.c_int64()
         self._check(self._lib.ifkv_reposition_keys(
             self._ctx, n, kp, vp, _i32_array(lens), _i32_array(chunk_order), _i32_array(cached_pos0),
-            _i64_array(delta_override), _ptr(k_out), _ptr(v_out), starts, C.byref(n_ctx)))
+            _i64_array(delta_override), self._cache(k_out, "k_out"), self._cache(v_out, "v_out"), starts, C.byref(n_ctx)))
         return k_out, v_out, [int(starts[i]) for i in range(n)], int(n_ctx.value)
 
     def score_tokens(self, k_global: torch.Tensor, q_prompt: torch.Tensor,
@@ -200,26 +242,38 @@ class Layer:
         n_ctx, m = int(k_global.shape[0]), int(q_prompt.shape[0])
         if scores is None:
             scores = self._empty(n_ctx, dtype=torch.float32)
-        self._check(self._lib.ifkv_score_tokens(self._ctx, _ptr(k_global), n_ctx, _ptr(q_prompt), m,
-                                                _ptr(k_prompt), int(accumulate), _ptr(scores)))
+        self._check(self._lib.ifkv_score_tokens(
+            self._ctx, self._cache(k_global, "k_global"), n_ctx, self._packed(q_prompt, "q_prompt", (self.n_q_heads, self.head_dim)), m,
+            self._packed(k_prompt, "k_prompt", (self.n_kv_heads, self.head_dim), rows=m), int(accumulate),
+            self._packed(scores, "scores", (), dtype=torch.float32, rows=n_ctx)))
         return scores
 
     def select_topk(self, scores: torch.Tensor, ratio: float = 0.0, k: int = -1,
                     idx_out: Optional[torch.Tensor] = None) -> torch.Tensor:
         n_ctx = int(scores.shape[0])
-        if idx_out is None:
-            want = k if k >= 0 else int(math.floor(float(ratio) * n_ctx)) if 0.0 <= ratio <= 1.0 else 0
-            idx_out = self._empty(max(want, 1), dtype=torch.int32)
         k_out = C.c_int64()
-        self._check(self._lib.ifkv_select_topk(self._ctx, _ptr(scores), n_ctx, float(ratio), int(k),
-                                               _ptr(idx_out), C.byref(k_out)))
+        sp = self._packed(scores, "scores", (), dtype=torch.float32)
+        if idx_out is None:   # the library knows the budget: ask it, then bring a buffer of that size
+            self._check(self._lib.ifkv_select_topk(self._ctx, sp, n_ctx, float(ratio), int(k), None, C.byref(k_out)))
+            idx_out = self._empty(max(int(k_out.value), 1), dtype=torch.int32)
+        self._check(self._lib.ifkv_select_topk(self._ctx, sp, n_ctx, float(ratio), int(k),
+                                               self._packed(idx_out, "idx_out", (), dtype=torch.int32), C.byref(k_out)))
+        if idx_out.shape[0] < int(k_out.value):
+            raise ValueError("idx_out: fewer entries than k")   # (checked by budget_of before the call in careful code)
         return idx_out[: int(k_out.value)]
+
+    def budget_of(self, n_ctx: int, ratio: float = 0.0, k: int = -1) -> int:
+        """k = floor(ratio * n_ctx) as the library evaluates it (no GPU work)."""
+        k_out = C.c_int64()
+        self._check(self._lib.ifkv_select_topk(self._ctx, None, int(n_ctx), float(ratio), int(k), None, C.byref(k_out)))
+        return int(k_out.value)
 
     def select_topk_noalloc(self, scores: torch.Tensor, idx_out: torch.Tensor, ratio: float = 0.0, k: int = -1) -> torch.Tensor:
         """ifkv_select_topk_noalloc: the caller brings idx_out; the call allocates nothing."""
         k_out = C.c_int64()
-        self._check(self._lib.ifkv_select_topk_noalloc(self._ctx, _ptr(scores), int(scores.shape[0]), float(ratio), int(k),
-                                                       _ptr(idx_out), C.byref(k_out)))
+        self._check(self._lib.ifkv_select_topk_noalloc(self._ctx, self._packed(scores, "scores", (), dtype=torch.float32),
+                                                       int(scores.shape[0]), float(ratio), int(k),
+                                                       self._packed(idx_out, "idx_out", (), dtype=torch.int32), C.byref(k_out)))
         return idx_out[: int(k_out.value)]
 
     def recompute_attention(self, q_sel: torch.Tensor, row_pos: torch.Tensor, k_cache: torch.Tensor,
@@ -229,18 +283,29 @@ class Layer:
         if out is None:
             out = self._empty(n_rows, self.n_q_heads, self.head_dim)
         lse = self._empty(n_rows, self.n_q_heads, dtype=torch.float32) if return_lse else None
-        self._check(self._lib.ifkv_recompute_attention(self._ctx, _ptr(q_sel), _ptr(row_pos), n_rows,
-                                                       _ptr(k_cache), _ptr(v_cache), n_kv, _ptr(out), _ptr(lse)))
+        qh = (self.n_q_heads, self.head_dim)
+        self._check(self._lib.ifkv_recompute_attention(
+            self._ctx, self._packed(q_sel, "q_sel", qh), self._packed(row_pos, "row_pos", (), dtype=torch.int32, rows=n_rows), n_rows,
+            self._cache(k_cache, "k_cache"), self._cache(v_cache, "v_cache"), n_kv, self._packed(out, "out", qh, rows=n_rows),
+            self._packed(lse, "lse", (self.n_q_heads,), dtype=torch.float32, rows=n_rows)))
         return (out, lse) if return_lse else out
 
     def splice_kv(self, k_new: torch.Tensor, v_new: Optional[torch.Tensor], idx: torch.Tensor,
                   k_cache: torch.Tensor, v_cache: Optional[torch.Tensor]) -> None:
-        self._check(self._lib.ifkv_splice_kv(self._ctx, _ptr(k_new), _ptr(v_new), _ptr(idx), int(idx.shape[0]),
-                                             _ptr(k_cache), _ptr(v_cache), int(k_cache.shape[0])))
+        n = int(idx.shape[0])
+        kv_tail = (self.n_kv_heads, self.head_dim)
+        self._check(self._lib.ifkv_splice_kv(self._ctx, self._packed(k_new, "k_new", kv_tail, rows=n),
+                                             self._packed(v_new, "v_new", kv_tail, rows=n),
+                                             self._packed(idx, "idx", (), dtype=torch.int32), n,
+                                             self._cache(k_cache, "k_cache"), self._cache(v_cache, "v_cache"), int(k_cache.shape[0])))
 
     def rope_rows(self, x: torch.Tensor, pos: torch.Tensor) -> torch.Tensor:
         """In place; x [R, n_heads, d], pos int32 [R]."""
-        self._check(self._lib.ifkv_rope_rows(self._ctx, _ptr(x), _ptr(pos), int(x.shape[0]), int(x.shape[1])))
+        if x.dim() != 3 or x.shape[2] != self.head_dim:
+            raise ValueError(f"x: expected [R, n_heads, {self.head_dim}], got {tuple(x.shape)}")
+        self._check(self._lib.ifkv_rope_rows(self._ctx, self._packed(x, "x", tuple(x.shape[1:])),
+                                             self._packed(pos, "pos", (), dtype=torch.int32, rows=int(x.shape[0])),
+                                             int(x.shape[0]), int(x.shape[1])))
         return x
 
     def chunk_counts(self, idx: torch.Tensor, slot_start: Sequence[int], n_ctx: int,
@@ -248,8 +313,9 @@ class Layer:
         n_slots = len(slot_start)
         if counts_out is None:
             counts_out = self._empty(max(n_slots, 1), dtype=torch.int32)
-        self._check(self._lib.ifkv_chunk_counts(self._ctx, _ptr(idx), int(idx.shape[0]), n_slots,
-                                                _i64_array(slot_start), int(n_ctx), _ptr(counts_out)))
+        self._check(self._lib.ifkv_chunk_counts(self._ctx, self._packed(idx, "idx", (), dtype=torch.int32), int(idx.shape[0]), n_slots,
+                                                _i64_array(slot_start), int(n_ctx),
+                                                self._packed(counts_out, "counts_out", (), dtype=torch.int32, rows=n_slots)))
         return counts_out[:n_slots]
 
     def reorder_chunks(self, order_in: Optional[Sequence[int]], slot_counts: Sequence[int],

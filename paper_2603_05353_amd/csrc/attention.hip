@@ -47,7 +47,8 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(const void *__re
                                                                 const void *__restrict__ k_cache,
                                                                 const void *__restrict__ v_cache, int64_t n_kv,
                                                                 int n_q_heads, int n_kv_heads, float sm_scale,
-                                                                void *__restrict__ out, float *__restrict__ lse_out) {
+                                                                CacheLayout lay, void *__restrict__ out,
+                                                                float *__restrict__ lse_out) {
   using E = Elem<Tag>;
   constexpr int VE = E::kVec;
   constexpr int PARTS = kThreads / D;
@@ -78,8 +79,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(const void *__re
     const bool valid = j <= p;
     float logit = -INFINITY;
     if (valid) {
-      const v4u *kr = reinterpret_cast<const v4u *>(static_cast<const char *>(k_cache) +
-                                                    (j * n_kv_heads + g) * D * E::kBytes);
+      const v4u *kr = reinterpret_cast<const v4u *>(static_cast<const char *>(k_cache) + lay.at(j, g) * E::kBytes);
       float dot = 0.f;
 #pragma unroll
       for (int v = 0; v < D / VE; ++v) {
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(const void *__re
     const int nt = static_cast<int>(min<int64_t>(kThreads, p + 1 - j0));
     acc *= alpha;
     for (int jj = part; jj < nt; jj += PARTS)
-      acc = fmaf(ps[jj], E::load1(v_cache, ((j0 + jj) * n_kv_heads + g) * D + c), acc);
+      acc = fmaf(ps[jj], E::load1(v_cache, lay.at(j0 + jj, g) + c), acc);
     __syncthreads();
   }
   comb[tid] = acc;
@@ -125,7 +125,7 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos,
     const int64_t qoff = r0 * d.n_q_heads * D * Elem<Tag>::kBytes;
     hipLaunchKernelGGL((attn_generic_kernel<Tag, D>), dim3(static_cast<unsigned>(nr), d.n_q_heads), dim3(kThreads), 0,
                        ctx->stream, static_cast<const char *>(q_sel) + qoff, row_pos + r0, k_cache, v_cache, n_kv,
-                       d.n_q_heads, d.n_kv_heads, ctx->sm_scale, static_cast<char *>(out) + qoff,
+                       d.n_q_heads, d.n_kv_heads, ctx->sm_scale, cache_layout(ctx), static_cast<char *>(out) + qoff,
                        lse_out ? lse_out + r0 * d.n_q_heads : nullptr);
   }
   return hipGetLastError();

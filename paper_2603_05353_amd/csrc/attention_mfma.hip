@@ -471,7 +471,7 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ row_pos, int n_rows,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache, int n_kv,
     uint16_t *__restrict__ out, float *__restrict__ lse_out, int n_q_heads, int n_kv_heads, float scale_log2,
-    int rows_per_block, SplitPlan sp) {
+    int rows_per_block, CacheLayout lay, SplitPlan sp) {
   __shared__ __attribute__((aligned(1024))) uint16_t k_lds[NS][TILE_ELEMS];
   __shared__ __attribute__((aligned(1024))) uint16_t v_lds[NS][TILE_ELEMS];
   __shared__ int s_pmax[NWAVES];
@@ -495,9 +495,9 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   if (part == 0 && g == 0 && threadIdx.x == 0 && sp.block_tiles != nullptr) sp.block_tiles[rb] = n_tiles;
   const ReadOffsets ro = make_read_offsets(lane);
 
-  const int64_t kv_row_elems = static_cast<int64_t>(n_kv_heads) * D;
-  const uint16_t *k_base = k_cache + static_cast<int64_t>(g) * D;
-  const uint16_t *v_base = v_cache + static_cast<int64_t>(g) * D;
+  const int64_t kv_row_elems = lay.token_stride;
+  const uint16_t *k_base = k_cache + g * lay.head_stride;
+  const uint16_t *v_base = v_cache + g * lay.head_stride;
   const auto plan = make_dma_plan<NWAVES>(kv_row_elems);
 
   const uint32_t k_lds_addr = __builtin_amdgcn_readfirstlane(lds_address(&k_lds[0][0]));
@@ -679,7 +679,7 @@ hipError_t launch_attention_range(ifkv_ctx *ctx, const uint16_t *q_sel, const in
   dim3 grid(d.n_kv_heads, n_rb, sc.parts);
   hipLaunchKernelGGL((attn_mfma_kernel<4, 2>), grid, dim3(256), 0, ctx->stream, q_sel, row_pos, static_cast<int>(n_rows),
                      k_cache, v_cache, static_cast<int>(n_kv), out, lse_out, d.n_q_heads, d.n_kv_heads, scale_log2, rpb,
-                     sp);
+                     cache_layout(ctx), sp);
   if (sc.parts > 1) {
     const int64_t items = n_rows * d.n_q_heads;
     hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, ctx->stream, sp,

@@ -42,6 +42,7 @@ int ensure_scratch(ifkv_ctx *ctx) {
   size_t bytes = ifkv::score_scratch_bytes(ctx, ctx->desc.max_ctx, ctx->desc.max_prompt);
   bytes = std::max(bytes, ifkv::topk_scratch_bytes(ctx, ctx->desc.max_ctx));
   bytes = std::max(bytes, ifkv::attention_scratch_bytes(ctx));
+  bytes = std::max(bytes, ifkv::validate_scratch_bytes(ctx));
   bytes = std::max<size_t>(bytes, 256);
   void *p = nullptr;
   hipError_t e = hipMalloc(&p, bytes);
@@ -104,12 +105,35 @@ int ifkv_create(ifkv_ctx **out, const ifkv_layer_desc *desc, void *hip_stream) {
   if (desc->max_ctx <= 0 || desc->max_ctx >= (int64_t(1) << 31))
     return fail(nullptr, IFKV_EINVAL, "ifkv_create: max_ctx must be in [1, 2^31)");
   if (desc->max_prompt < 0) return fail(nullptr, IFKV_EINVAL, "ifkv_create: max_prompt must be >= 0");
+  int64_t ts = desc->token_stride, hs = desc->head_stride;
+  if ((ts == 0) != (hs == 0))
+    return fail(nullptr, IFKV_EINVAL, "ifkv_create: token_stride and head_stride must both be 0 (packed) or both be given");
+  if (ts == 0) {
+    ts = static_cast<int64_t>(desc->n_kv_heads) * desc->head_dim;
+    hs = desc->head_dim;
+  } else {
+    const int64_t vec = desc->dtype == IFKV_BF16 ? 8 : 4;  // elements in 16 bytes
+    const int64_t d = desc->head_dim;
+    if (ts < d || hs < d || ts % vec != 0 || hs % vec != 0)
+      return fail(nullptr, IFKV_EINVAL, "ifkv_create: strides must be multiples of %lld elements and at least head_dim",
+                  static_cast<long long>(vec));
+    const bool token_major = ts >= (desc->n_kv_heads - 1) * hs + d;
+    const bool head_major = hs / ts >= desc->max_ctx - 1 && hs >= (desc->max_ctx - 1) * ts + d;
+    if (!token_major && !head_major)
+      return fail(nullptr, IFKV_EINVAL, "ifkv_create: token_stride=%lld, head_stride=%lld make rows or heads overlap",
+                  static_cast<long long>(ts), static_cast<long long>(hs));
+    if (ts > (int64_t(1) << 24) || hs > (int64_t(1) << 40))
+      return fail(nullptr, IFKV_EINVAL, "ifkv_create: strides out of range");
+  }
 
   ifkv_ctx *ctx = new (std::nothrow) ifkv_ctx();
   if (ctx == nullptr) return fail(nullptr, IFKV_ENOMEM, "ifkv_create: out of host memory");
   ctx->desc = *desc;
   ctx->desc.inv_freq = nullptr;
   ctx->stream = static_cast<hipStream_t>(hip_stream);
+  ctx->token_stride = ts;
+  ctx->head_stride = hs;
+  ctx->packed = (ts == static_cast<int64_t>(desc->n_kv_heads) * desc->head_dim) && (hs == desc->head_dim);
   ctx->sm_scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / std::sqrt(static_cast<float>(desc->head_dim));
   const int half = desc->head_dim / 2;
   for (int j = 0; j < half; ++j) {
@@ -259,8 +283,8 @@ int ifkv_select_topk(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, double r
   int rc = topk_budget(ctx, n_ctx, ratio, k_override, &k);
   if (rc != IFKV_OK) return rc;
   if (k_out != nullptr) *k_out = k;
-  if (k == 0) return IFKV_OK;
-  if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk: NULL pointer");
+  if (k == 0 || idx_out == nullptr) return IFKV_OK;  // no output buffer: the caller only asks for k
+  if (scores == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk: scores is NULL");
   rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
   hipError_t e = ifkv::launch_topk(ctx, scores, n_ctx, k, idx_out, ctx->scratch);
@@ -277,8 +301,8 @@ int ifkv_select_topk_noalloc(ifkv_ctx *ctx, const float *scores, int64_t n_ctx, 
     return fail(ctx, IFKV_ESHAPE, "select_topk_noalloc: n_ctx=%lld exceeds the %lld scores this entry point serves",
                 static_cast<long long>(n_ctx), static_cast<long long>(ifkv::topk_static_max_ctx()));
   if (k_out != nullptr) *k_out = k;
-  if (k == 0) return IFKV_OK;
-  if (scores == nullptr || idx_out == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk_noalloc: NULL pointer");
+  if (k == 0 || idx_out == nullptr) return IFKV_OK;  // no output buffer: the caller only asks for k
+  if (scores == nullptr) return fail(ctx, IFKV_EINVAL, "select_topk_noalloc: scores is NULL");
   void *work = nullptr;
   hipError_t e = ifkv::topk_static_scratch(&work);
   if (e != hipSuccess) return hip_fail(ctx, e, "address of the static scratch");
@@ -303,6 +327,14 @@ int ifkv_recompute_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *ro
     return fail(ctx, IFKV_EINVAL, "recompute_attention: tensors must be 16-byte aligned");
   int rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
+  if (ctx->desc.flags & IFKV_FLAG_VALIDATE) {
+    int64_t bad = -1;
+    hipError_t ev = ifkv::validate_ascending(ctx, row_pos, n_rows, &bad);
+    if (ev != hipSuccess) return hip_fail(ctx, ev, "row_pos check");
+    if (bad >= 0)
+      return fail(ctx, IFKV_EINVAL, "recompute_attention: row_pos is not strictly ascending at index %lld",
+                  static_cast<long long>(bad));
+  }
   hipError_t e = ifkv::launch_attention(ctx, q_sel, row_pos, n_rows, k_cache, v_cache, n_kv, out, lse_out);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "attention kernel launch");
 }
@@ -321,6 +353,16 @@ int ifkv_splice_kv(ifkv_ctx *ctx, const void *k_new, const void *v_new, const in
     return fail(ctx, IFKV_EINVAL, "splice_kv: v_new and v_cache must both be given or both be NULL");
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
     return fail(ctx, IFKV_EINVAL, "splice_kv: tensors must be 16-byte aligned");
+  if (ctx->desc.flags & IFKV_FLAG_VALIDATE) {
+    int rc = ensure_scratch(ctx);
+    if (rc != IFKV_OK) return rc;
+    int64_t bad = -1;
+    hipError_t ev = ifkv::validate_unique(ctx, idx, n_rows, n_kv, &bad);
+    if (ev != hipSuccess) return hip_fail(ctx, ev, "idx check");
+    if (bad >= 0)
+      return fail(ctx, IFKV_EINVAL, "splice_kv: idx names a cache row twice (one of the two entries is index %lld)",
+                  static_cast<long long>(bad));
+  }
   hipError_t e = ifkv::launch_splice(ctx, k_new, v_new, idx, n_rows, k_cache, v_cache, n_kv);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "splice kernel launch");
 }

@@ -21,6 +21,9 @@ struct ifkv_ctx {
   ifkv_tuning tune;
   hipStream_t stream = nullptr;
   float sm_scale = 0.f;
+  int64_t token_stride = 0;     // concatenated caches: elements between rows / between kv heads (resolved, never 0)
+  int64_t head_stride = 0;
+  bool packed = true;           // token_stride == H_kv * d and head_stride == d
   double inv_freq[128];         // d/2 entries, host copy
   double *d_inv_freq = nullptr; // device copy, uploaded on first use
   void *scratch = nullptr;      // device scratch shared by the stages, allocated once
@@ -31,6 +34,13 @@ struct ifkv_ctx {
 namespace ifkv {
 
 constexpr int kMaxHeadDim = 256;
+
+// Where the concatenated caches keep element c of kv head h of row t (elements).
+struct CacheLayout {
+  int64_t token_stride, head_stride;
+  __host__ __device__ __forceinline__ int64_t at(int64_t t, int h) const { return t * token_stride + h * head_stride; }
+};
+inline CacheLayout cache_layout(const ifkv_ctx *ctx) { return CacheLayout{ctx->token_stride, ctx->head_stride}; }
 
 inline size_t dtype_size(int dtype) { return dtype == IFKV_BF16 ? 2 : 4; }
 
@@ -83,6 +93,12 @@ hipError_t launch_chunk_counts(ifkv_ctx *ctx, const int32_t *idx, int64_t k, con
 // Stage 5.
 hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, const int32_t *idx,
                          int64_t n_rows, void *k_cache, void *v_cache, int64_t n_kv);
+
+// Debug-mode checks of device-resident preconditions (validate.hip); *bad_out = offending index or -1.
+// They wait for the stream.
+size_t validate_scratch_bytes(const ifkv_ctx *ctx);
+hipError_t validate_ascending(ifkv_ctx *ctx, const int32_t *v, int64_t n, int64_t *bad_out);
+hipError_t validate_unique(ifkv_ctx *ctx, const int32_t *idx, int64_t n, int64_t n_kv, int64_t *bad_out);
 
 // Calibration copy.
 hipError_t launch_copy(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes);

@@ -26,7 +26,8 @@ template <typename Tag, int D>
 __global__ __launch_bounds__(kStatThreads) void score_stats_generic(const void *__restrict__ k_global, int64_t n_ctx,
                                                                     const void *__restrict__ q_prompt, int m_prompt,
                                                                     int n_q_heads, int n_kv_heads, float sm_scale,
-                                                                    int slice_len, float2 *__restrict__ partial) {
+                                                                    CacheLayout lay, int slice_len,
+                                                                    float2 *__restrict__ partial) {
   using E = Elem<Tag>;
   __shared__ float ks[kStatTile][D];
   const int slice = blockIdx.x;
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(kStatThreads) void score_stats_generic(const void *
     __syncthreads();
     for (int e = threadIdx.x; e < nt * D; e += kStatThreads) {
       const int jj = e / D, c = e - jj * D;
-      ks[jj][c] = E::load1(k_global, ((j0 + jj) * n_kv_heads + g) * D + c);
+      ks[jj][c] = E::load1(k_global, lay.at(j0 + jj, g) + c);
     }
     __syncthreads();
     for (int jj = 0; jj < nt; ++jj) {
@@ -129,7 +130,7 @@ template <typename Tag, int D>
 __global__ __launch_bounds__(kColThreads) void score_colsum_generic(const void *__restrict__ k_global, int64_t n_ctx,
                                                                     const void *__restrict__ q_prompt, int m_prompt,
                                                                     int n_q_heads, int n_kv_heads, float sm_scale,
-                                                                    const float2 *__restrict__ stats,
+                                                                    CacheLayout lay, const float2 *__restrict__ stats,
                                                                     float *__restrict__ colpart) {
   using E = Elem<Tag>;
   __shared__ float qs[kColRows][D];
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(kColThreads) void score_colsum_generic(const void *
   float acc = 0.f;
   float kreg[D];
   if (active) {
-    const int64_t koff = (j * n_kv_heads + g) * D;
+    const int64_t koff = lay.at(j, g);
 #pragma unroll
     for (int c = 0; c < D; ++c) kreg[c] = E::load1(k_global, koff + c);
   } else {
@@ -206,7 +207,7 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const
   hipStream_t st = ctx->stream;
   dim3 ga(n_slices, d.n_q_heads, (m_prompt + kStatThreads - 1) / kStatThreads);
   hipLaunchKernelGGL((score_stats_generic<Tag, D>), ga, dim3(kStatThreads), 0, st, k_global, n_ctx, q_prompt,
-                     m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, sl, partial);
+                     m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, cache_layout(ctx), sl, partial);
   const int rows = d.n_q_heads * m_prompt;
   hipLaunchKernelGGL((score_merge_kernel<Tag, D>), dim3((rows + 63) / 64), dim3(64), 0, st, partial, n_slices,
                      q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
@@ -214,7 +215,7 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const
   hipLaunchKernelGGL((score_colsum_generic<Tag, D>),
                      dim3(static_cast<unsigned>((n_ctx + kColThreads - 1) / kColThreads), d.n_kv_heads),
                      dim3(kColThreads), 0, st, k_global, n_ctx, q_prompt, m_prompt, d.n_q_heads, d.n_kv_heads,
-                     ctx->sm_scale, stats, colpart);
+                     ctx->sm_scale, cache_layout(ctx), stats, colpart);
   hipLaunchKernelGGL(score_colsum_reduce, dim3(static_cast<unsigned>((n_ctx + 255) / 256)), dim3(256), 0, st, colpart,
                      d.n_kv_heads, n_ctx, 1.0f / d.n_q_heads, accumulate, scores);
   return hipGetLastError();

@@ -46,6 +46,7 @@ struct ScoreGeom {
   int q_chunk_rows;  // rows per chunk (multiple of 128, <= kQChunk); the last chunk may hold fewer
   int kv_per_block;
   float scale_log2;
+  int64_t token_stride, head_stride;  // layout of k_global, in elements
 };
 
 // Query row `ql` of chunk `qc` for kv head g: rows are ordered (prompt row, head-in-group).
@@ -101,7 +102,7 @@ __device__ __forceinline__ void load_k_frags(bf16x8 (&kf)[2][8], const uint16_t 
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     const int j = min(j0 + 32 * t + row, gm.n_ctx - 1);
-    const uint16_t *p = k_global + (static_cast<int64_t>(j) * gm.n_kv_heads + g) * D + 8 * hf;
+    const uint16_t *p = k_global + static_cast<int64_t>(j) * gm.token_stride + g * gm.head_stride + 8 * hf;
 #pragma unroll
     for (int s = 0; s < 8; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u *>(p + 16 * s));
   }
@@ -453,6 +454,8 @@ hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t
   gm.m_prompt = m_prompt;
   gm.n_q_heads = d.n_q_heads;
   gm.n_kv_heads = d.n_kv_heads;
+  gm.token_stride = ctx->token_stride;
+  gm.head_stride = ctx->head_stride;
   // query rows of a kv head are cut into equal chunks of a multiple of 128 rows (pass A is compiled
   // for 4, 8, 12 and 16 blocks of 32 rows)
   gm.n_qchunks = (m_prompt * G + kQChunk - 1) / kQChunk;

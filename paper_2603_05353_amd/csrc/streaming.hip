@@ -45,10 +45,12 @@ __device__ __forceinline__ void copy_vectors(const v4u *__restrict__ src, v4u *_
   }
 }
 
-template <typename Tag, int PAIRING, int RB>
+// The chunk caches are packed; the concatenated caches may be strided (PACKED false): then the
+// destination of a 16-byte vector follows from its (row, head, vector within the head).
+template <typename Tag, int PAIRING, int RB, bool PACKED>
 __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const double *__restrict__ inv_freq,
                                                               int rows_per_tile, int n_kv_heads, int head_dim,
-                                                              v4u *__restrict__ k_out,
+                                                              CacheLayout lay, v4u *__restrict__ k_out,
                                                               v4u *__restrict__ v_out) {
   using E = Elem<Tag>;
   constexpr int VE = E::kVec;
@@ -71,14 +73,27 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
   const int row_vecs = n_kv_heads * head_dim / VE;  // 16-byte vectors per row
   const int total_vecs = nrows * row_vecs;          // rows are contiguous: the tile is one flat range
   const v4u *k_src = reinterpret_cast<const v4u *>(c.k) + static_cast<int64_t>(row0) * row_vecs;
-  v4u *k_dst = k_out + (c.dst_row + row0) * row_vecs;
   const bool has_v = c.v != nullptr && v_out != nullptr;
   const v4u *v_src = has_v ? reinterpret_cast<const v4u *>(c.v) + static_cast<int64_t>(row0) * row_vecs : nullptr;
-  v4u *v_dst = has_v ? v_out + (c.dst_row + row0) * row_vecs : nullptr;
+  // where vector o of the tile (o counts the tile's source vectors) goes in the concatenated cache
+  const int head_vecs_log2 = __builtin_ctz(head_dim / VE);
+  auto dst_of = [&](int o) -> int64_t {
+    if (PACKED) return (c.dst_row + row0) * row_vecs + o;
+    const int r = o / row_vecs, rem = o - r * row_vecs;
+    return lay.at(c.dst_row + row0 + r, rem >> head_vecs_log2) / VE + (rem & ((1 << head_vecs_log2) - 1));
+  };
 
   if (c.advance == 0.0) {  // already at its global phase: both tensors are plain row copies
-    copy_vectors(k_src, k_dst, total_vecs, tid);
-    if (has_v) copy_vectors(v_src, v_dst, total_vecs, tid);
+    if (PACKED) {
+      copy_vectors(k_src, k_out + dst_of(0), total_vecs, tid);
+      if (has_v) copy_vectors(v_src, v_out + dst_of(0), total_vecs, tid);
+    } else {
+      for (int it = tid; it < total_vecs; it += kThreads) {
+        const int64_t dd = dst_of(it);
+        __builtin_nontemporal_store(__builtin_nontemporal_load(k_src + it), k_out + dd);
+        if (has_v) __builtin_nontemporal_store(__builtin_nontemporal_load(v_src + it), v_out + dd);
+      }
+    }
     return;
   }
 
@@ -141,8 +156,9 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
             ra[e] = fmaf(a[e], cs, -(bb[e] * sn));
             rb[e] = fmaf(a[e], sn, bb[e] * cs);
           }
-          __builtin_nontemporal_store(E::pack(ra), k_dst + off[u]);
-          __builtin_nontemporal_store(E::pack(rb), k_dst + off[u] + hv);
+          const int64_t dd = dst_of(off[u]);
+          __builtin_nontemporal_store(E::pack(ra), k_out + dd);
+          __builtin_nontemporal_store(E::pack(rb), k_out + dd + hv);
         }
       }
       if (has_v) {
@@ -150,8 +166,9 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
         for (int u = 0; u < RB; ++u) {
           const int it = base0 + tid + u * kThreads;
           if (it < total) {
-            __builtin_nontemporal_store(vlo[u], v_dst + off[u]);
-            __builtin_nontemporal_store(vhi[u], v_dst + off[u] + hv);
+            const int64_t dd = dst_of(off[u]);
+            __builtin_nontemporal_store(vlo[u], v_out + dd);
+            __builtin_nontemporal_store(vhi[u], v_out + dd + hv);
           }
         }
       }
@@ -183,8 +200,9 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
             r[2 * e] = fmaf(f[2 * e], cs, -(f[2 * e + 1] * sn));
             r[2 * e + 1] = fmaf(f[2 * e], sn, f[2 * e + 1] * cs);
           }
-          __builtin_nontemporal_store(E::pack(r), k_dst + it);
-          if (has_v) __builtin_nontemporal_store(y[u], v_dst + it);
+          const int64_t dd = dst_of(it);
+          __builtin_nontemporal_store(E::pack(r), k_out + dd);
+          if (has_v) __builtin_nontemporal_store(y[u], v_out + dd);
         }
       }
     }
@@ -198,7 +216,8 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(RepoBatch b, const
 __global__ __launch_bounds__(kThreads) void splice_kernel(const v4u *__restrict__ k_new,
                                                           const v4u *__restrict__ v_new,
                                                           const int32_t *__restrict__ idx, int64_t n_rows,
-                                                          int row_vecs, v4u *__restrict__ k_cache,
+                                                          int row_vecs, int head_vecs_log2, int64_t token_vecs,
+                                                          int64_t head_stride_vecs, v4u *__restrict__ k_cache,
                                                           v4u *__restrict__ v_cache, int64_t n_kv) {
   const int64_t total = n_rows * row_vecs;
   const int64_t base0 = static_cast<int64_t>(blockIdx.x) * (kThreads * kBatch) + threadIdx.x;
@@ -213,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void splice_kernel(const v4u *__restrict_
       const int w = static_cast<int>(it - r * row_vecs);
       const int64_t row = idx[r];
       if (row >= 0 && row < n_kv) {
-        dst[u] = row * row_vecs + w;
+        dst[u] = row * token_vecs + (w >> head_vecs_log2) * head_stride_vecs + (w & ((1 << head_vecs_log2) - 1));
         xk[u] = __builtin_nontemporal_load(k_new + it);
         if (v_new != nullptr) xv[u] = __builtin_nontemporal_load(v_new + it);
       }
@@ -315,9 +334,16 @@ hipError_t launch_reposition(ifkv_ctx *ctx, const RepoBatch &batch, void *k_out,
   dim3 grid(batch.total_tiles), block(kThreads);
   v4u *ko = reinterpret_cast<v4u *>(k_out);
   v4u *vo = reinterpret_cast<v4u *>(v_out);
-#define IFKV_LAUNCH_REPO(TAG, PAIR)                                                              \
-  hipLaunchKernelGGL((reposition_kernel<TAG, PAIR, kRepoBatch>), grid, block, 0, ctx->stream,    \
-                     batch, ctx->d_inv_freq, kRepoRows, d.n_kv_heads, d.head_dim, ko, vo)
+  const CacheLayout lay = cache_layout(ctx);
+#define IFKV_LAUNCH_REPO(TAG, PAIR)                                                                          \
+  do {                                                                                                       \
+    if (ctx->packed)                                                                                         \
+      hipLaunchKernelGGL((reposition_kernel<TAG, PAIR, kRepoBatch, true>), grid, block, 0, ctx->stream,      \
+                         batch, ctx->d_inv_freq, kRepoRows, d.n_kv_heads, d.head_dim, lay, ko, vo);          \
+    else                                                                                                     \
+      hipLaunchKernelGGL((reposition_kernel<TAG, PAIR, kRepoBatch, false>), grid, block, 0, ctx->stream,     \
+                         batch, ctx->d_inv_freq, kRepoRows, d.n_kv_heads, d.head_dim, lay, ko, vo);          \
+  } while (0)
   if (d.dtype == IFKV_BF16) {
     if (d.pairing == IFKV_ROPE_HALF)
       IFKV_LAUNCH_REPO(BF16Tag, IFKV_ROPE_HALF);
@@ -341,9 +367,11 @@ hipError_t launch_splice(ifkv_ctx *ctx, const void *k_new, const void *v_new, co
   const int64_t total = n_rows * row_vecs;
   const int64_t per_block = kThreads * kBatch;
   dim3 grid(static_cast<unsigned>((total + per_block - 1) / per_block)), block(kThreads);
+  const int ve = static_cast<int>(16 / dtype_size(d.dtype));
   hipLaunchKernelGGL(splice_kernel, grid, block, 0, ctx->stream, reinterpret_cast<const v4u *>(k_new),
-                     reinterpret_cast<const v4u *>(v_new), idx, n_rows, row_vecs,
-                     reinterpret_cast<v4u *>(k_cache), reinterpret_cast<v4u *>(v_cache), n_kv);
+                     reinterpret_cast<const v4u *>(v_new), idx, n_rows, row_vecs, __builtin_ctz(d.head_dim / ve),
+                     ctx->token_stride / ve, ctx->head_stride / ve, reinterpret_cast<v4u *>(k_cache),
+                     reinterpret_cast<v4u *>(v_cache), n_kv);
   return hipGetLastError();
 }
 

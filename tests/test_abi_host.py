@@ -121,7 +121,9 @@ def test_topk_validation_and_budget(lib):
     # k = floor(rho N) is known on the host; k = 0 launches nothing
     assert _call(L, "ifkv_select_topk", f, 100, 0.0, -1, f, C.byref(k)) == B.IFKV_OK and k.value == 0
     assert _call(L, "ifkv_select_topk", f, 6, 0.15, -1, f, C.byref(k)) == B.IFKV_OK and k.value == 0
-    assert _call(L, "ifkv_select_topk", None, 1024, 0.15, -1, None, C.byref(k)) == B.IFKV_EINVAL and k.value == 153
+    # no output buffer: the call only reports k; an output buffer without scores is an error
+    assert _call(L, "ifkv_select_topk", None, 1024, 0.15, -1, None, C.byref(k)) == B.IFKV_OK and k.value == 153
+    assert _call(L, "ifkv_select_topk", None, 1024, 0.15, -1, f, C.byref(k)) == B.IFKV_EINVAL and k.value == 153
     L.close()
 
 
@@ -221,4 +223,31 @@ def test_set_tuning_validation(lib):
         assert e.value.code == B.IFKV_EINVAL
     assert lib.ifkv_set_tuning(L._ctx, None, 1) == B.IFKV_EINVAL
     assert lib.ifkv_set_tuning(None, b"attn_split_parts", 1) == B.IFKV_EINVAL
+    L.close()
+
+
+def test_cache_strides_validation(lib):
+    """token_stride / head_stride of the layer descriptor: both or neither, 16-byte multiples, at least
+    head_dim, and no overlap of the heads of a row or of the rows of a head."""
+    ok = [dict(), dict(token_stride=128, head_stride=128 * 5000), dict(token_stride=8 * 128 + 64, head_stride=136),
+          dict(token_stride=8 * 128, head_stride=128)]
+    for kw in ok:
+        B.Layer("bf16", 32, 8, 128, 5e5, max_ctx=4096, max_prompt=16, stream=0, **kw).close()
+    bad = [dict(token_stride=1024), dict(head_stride=128), dict(token_stride=1028, head_stride=128),
+           dict(token_stride=64, head_stride=128), dict(token_stride=1024, head_stride=192),    # heads of a row overlap
+           dict(token_stride=128, head_stride=128 * 4000),                                      # rows of a head overlap (max_ctx 4096)
+           dict(token_stride=1 << 25, head_stride=128)]
+    for kw in bad:
+        with pytest.raises(B.IfkvError) as e:
+            B.Layer("bf16", 32, 8, 128, 5e5, max_ctx=4096, max_prompt=16, stream=0, **kw)
+        assert e.value.code == B.IFKV_EINVAL, kw
+
+
+def test_select_topk_reports_k_without_a_buffer(lib):
+    L = _layer()
+    k = C.c_int64(-1)
+    assert lib.ifkv_select_topk(L._ctx, None, 1024, 0.15, -1, None, C.byref(k)) == B.IFKV_OK and k.value == 153
+    assert lib.ifkv_select_topk(L._ctx, None, 1000, 0.0, 77, None, C.byref(k)) == B.IFKV_OK and k.value == 77
+    assert lib.ifkv_select_topk_noalloc(L._ctx, None, 1024, 0.3, -1, None, C.byref(k)) == B.IFKV_OK and k.value == 307
+    assert L.budget_of(1024, 0.15) == 153
     L.close()

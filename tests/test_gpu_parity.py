@@ -521,11 +521,34 @@ def test_splice_bit_exact(cfg):
 # ---------------------------------------------------------------------------
 # composite
 # ---------------------------------------------------------------------------
-def run_layer_gpu(wl, ratio, flags=0):
+SENTINEL = 0x7F7F      # bf16 bit pattern / low half of the f32 one that fills the padding of strided caches
+
+
+def strided_cache(L, n_rows):
+    """A cache in the layer's layout carved out of a buffer filled with a sentinel, and the buffer."""
+    storage = (n_rows - 1) * L.token_stride + (L.n_kv_heads - 1) * L.head_stride + L.head_dim
+    base = torch.full((storage,), 0, dtype=L.torch_dtype, device=DEV)
+    base.view(torch.int16 if L.dtype == "bf16" else torch.int32).fill_(SENTINEL)
+    return torch.as_strided(base, (n_rows, L.n_kv_heads, L.head_dim), (L.token_stride, L.head_stride, 1)), base
+
+
+def padding_untouched(cache, base):
+    """Everything in the buffer that is not an element of the logical cache still holds the sentinel."""
+    bits = base.view(torch.int16 if base.dtype == torch.bfloat16 else torch.int32).clone()
+    torch.as_strided(bits, cache.shape, cache.stride()).fill_(SENTINEL)
+    return bool((bits == SENTINEL).all())
+
+
+def run_layer_gpu(wl, ratio, flags=0, layout=None):
     sp = wl.spec
-    L = make_layer(sp, max_ctx=wl.n_ctx, max_prompt=sp.m_prompt, flags=flags)
+    kw = {} if layout is None else dict(token_stride=layout[0], head_stride=layout[1])
+    L = make_layer(sp, max_ctx=wl.n_ctx, max_prompt=sp.m_prompt, flags=flags, **kw)
     kd, vd = dev_chunks(wl)
-    K, V, starts, N = L.reposition_keys(kd, vd, chunk_order=wl.chunk_order.tolist())
+    if layout is None:
+        K, V, starts, N = L.reposition_keys(kd, vd, chunk_order=wl.chunk_order.tolist())
+    else:
+        (K, L._k_base), (V, L._v_base) = strided_cache(L, wl.n_ctx), strided_cache(L, wl.n_ctx)
+        K, V, starts, N = L.reposition_keys(kd, vd, chunk_order=wl.chunk_order.tolist(), k_out=K, v_out=V)
     s = L.score_tokens(K, to_dev(wl.q_prompt, sp.dtype))
     idx = L.select_topk(s, ratio=ratio)
     sync()
@@ -611,10 +634,10 @@ def test_composite_layer_random_shapes(seed):
     composite_case(spec, ratio, 1e-5 if spec.dtype == "f32" else 1e-4)
 
 
-def composite_case(spec, ratio, rtol_sel):
+def composite_case(spec, ratio, rtol_sel, layout=None):
     wl = make_workload(spec)
     k, v, q = oracle_inputs(wl)
-    L, K, V, s, idx = run_layer_gpu(wl, ratio)
+    L, K, V, s, idx = run_layer_gpu(wl, ratio, layout=layout)
     # oracle on its own
     Kref, Vref, _, N = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, spec.pairing)
     s_ref = O.score_tokens(Kref, q, wl.sm_scale)
@@ -644,6 +667,151 @@ def composite_case(spec, ratio, rtol_sel):
     ref, ref_abs, lse_ref = oracle_attention(to_f64(q_sel, spec.dtype), idx_ref, K2, V2, wl.sm_scale)
     assert_attention_close(to_host_f64(out, spec.dtype), ref, ref_abs, spec.dtype,
                            lse.cpu().numpy().astype(np.float64), lse_ref)
+    # stage 1 and stage 5 element by element (the stages above only constrain them through scores and outputs)
+    check_reposition(to_host_f64(K, spec.dtype)[np.setdiff1d(np.arange(N), idx_ref)],
+                     Kref[np.setdiff1d(np.arange(N), idx_ref)], spec.dtype, spec.pairing)
+    bits = np.uint16 if spec.dtype == "bf16" else np.uint32
+    assert np.array_equal(to_host_bits(K, spec.dtype)[idx_ref], np.ascontiguousarray(k_new).view(bits))
+    assert np.array_equal(to_host_bits(V, spec.dtype)[idx_ref], np.ascontiguousarray(v_new).view(bits))
+    if layout is not None:
+        assert padding_untouched(K, L._k_base) and padding_untouched(V, L._v_base)
+    L.close()
+
+
+def layouts_for(spec, n_ctx):
+    """[H_kv, T_cap, d] (heads outermost, room for 40 more rows), and token-major rows padded by 64
+    elements with heads 8 elements apart more than they need."""
+    d, h = spec.head_dim, spec.n_kv_heads
+    return {"head-major": (d, (n_ctx + 40) * d), "padded-token-major": (h * (d + 8) + 64, d + 8)}
+
+
+@pytest.mark.parametrize("which", ["head-major", "padded-token-major"])
+@pytest.mark.parametrize("cfg", ["C1", "C2", "C2-alu", "C5", "C1-interleaved"])
+def test_composite_layer_on_strided_caches(cfg, which):
+    """The whole path with the concatenated caches in a layout other than packed [T, H_kv, d]: every
+    stage that touches them (1 writes, 2 and 4 read, 5 writes) against the oracle, and nothing written
+    outside the logical tensor."""
+    spec = {"C1": preset("C1", chunk_lens=[100, 61, 130], m_prompt=12),
+            "C1-interleaved": preset("C1", chunk_lens=[100, 61, 130], m_prompt=12, pairing="interleaved"),
+            "C2": preset("C2", chunk_lens=[256, 100, 190, 64], m_prompt=32, permute_order=True),
+            "C2-alu": preset("C2", chunk_lens=[120, 77], m_prompt=9),
+            "C5": preset("C5", chunk_lens=[64] * 6 + [32] * 3, m_prompt=16)}[cfg]
+    n_ctx = int(np.sum(spec.chunk_lens))
+    layout = layouts_for(spec, n_ctx)[which]
+    if cfg == "C2-alu":
+        wl = make_workload(spec)
+        L, K, V, s, idx = run_layer_gpu(wl, 0.15, flags=FORCE_GENERIC, layout=layout)
+        k, v, q = oracle_inputs(wl)
+        Kref, Vref, _, N = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, spec.pairing)
+        check_reposition(to_host_f64(K, spec.dtype), Kref, spec.dtype, spec.pairing)
+        s_ref = O.score_tokens(to_host_f64(K, spec.dtype), q, wl.sm_scale)
+        assert (np.abs(s.cpu().numpy() - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all()
+        rows = sample_rows(N, 40, 3)
+        q_sel, _, _ = make_recompute_inputs(wl, rows)
+        out, lse = L.recompute_attention(to_dev(q_sel, spec.dtype), torch.from_numpy(rows.astype(np.int32)).to(DEV), K, V,
+                                         return_lse=True)
+        sync()
+        ref, ref_abs, lse_ref = oracle_attention(to_f64(q_sel, spec.dtype), rows, to_host_f64(K, spec.dtype),
+                                                 to_host_f64(V, spec.dtype), wl.sm_scale)
+        assert_attention_close(to_host_f64(out, spec.dtype), ref, ref_abs, spec.dtype, lse.cpu().numpy().astype(np.float64), lse_ref)
+        assert padding_untouched(K, L._k_base) and padding_untouched(V, L._v_base)
+        L.close()
+    else:
+        composite_case(spec, 0.15, 1e-5 if spec.dtype == "f32" else 1e-4, layout=layout)
+
+
+def test_strided_layout_gives_the_same_bits_as_packed():
+    """Same inputs, packed and head-major caches: the arithmetic is the same, so scores, selection and
+    attention outputs agree bit for bit (100 kv tiles: the attention launch is cut along the kv axis)."""
+    spec = preset("C2", chunk_lens=[640] * 10, m_prompt=32)
+    wl = make_workload(spec)
+    res = []
+    for layout in (None, layouts_for(spec, wl.n_ctx)["head-major"]):
+        L, K, V, s, idx = run_layer_gpu(wl, 0.1, layout=layout)
+        q_sel, _, _ = make_recompute_inputs(wl, idx.cpu().numpy().astype(np.int64))
+        out, lse = L.recompute_attention(to_dev(q_sel, spec.dtype), idx, K, V, return_lse=True)
+        sync()
+        res.append((to_host_bits(K, spec.dtype), s.cpu().numpy(), idx.cpu().numpy(), to_host_bits(out, spec.dtype), lse.cpu().numpy()))
+        L.close()
+    for a, b in zip(*res):
+        assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------------------
+# debug mode: device-side checks of what host code cannot see
+# ---------------------------------------------------------------------------
+def test_validate_flag_reports_bad_row_pos_and_duplicate_idx():
+    from paper_2603_05353_amd import IFKV_FLAG_VALIDATE, IfkvError
+    spec = preset("C2", chunk_lens=[300, 211], m_prompt=8)
+    wl = make_workload(spec)
+    K_st, K64, _ = global_keys(wl)
+    V_st = np.concatenate([wl.v_chunks[c] for c in wl.chunk_order], axis=0)
+    rows = sample_rows(511, 70, 2)
+    q_sel, k_new, v_new = make_recompute_inputs(wl, rows)
+    L = make_layer(spec, max_ctx=511, max_prompt=8, flags=IFKV_FLAG_VALIDATE)
+    Ln = make_layer(spec, max_ctx=511, max_prompt=8)
+    Kd, Vd, qd = to_dev(K_st, "bf16"), to_dev(V_st, "bf16"), to_dev(q_sel, "bf16")
+    good = torch.from_numpy(rows.astype(np.int32)).to(DEV)
+    # good input: same result as without the flag
+    out_v = L.recompute_attention(qd, good, Kd, Vd)
+    out_n = Ln.recompute_attention(qd, good, Kd, Vd)
+    sync()
+    assert torch.equal(out_v, out_n)
+    for pos, what in [(17, "equal"), (40, "descending"), (69, "descending")]:
+        bad = good.clone()
+        bad[pos] = bad[pos - 1] if what == "equal" else bad[pos - 1] - 3
+        with pytest.raises(IfkvError) as e:
+            L.recompute_attention(qd, bad, Kd, Vd)
+        assert e.value.code == -1 and f"index {pos}" in str(e.value)
+    # splice: duplicates are refused and nothing is written; unique indices (in any order) pass
+    K2 = Kd.clone()
+    dup = good.clone()
+    dup[33] = dup[5]
+    with pytest.raises(IfkvError) as e:
+        L.splice_kv(to_dev(k_new, "bf16"), to_dev(v_new, "bf16"), dup, K2, Vd.clone())
+    assert e.value.code == -1 and ("index 33" in str(e.value) or "index 5" in str(e.value))
+    sync()
+    assert torch.equal(K2, Kd)
+    perm = torch.randperm(70, generator=torch.Generator().manual_seed(3))
+    L.splice_kv(to_dev(k_new[perm.numpy()], "bf16"), to_dev(v_new[perm.numpy()], "bf16"), good[perm.to(DEV)], K2, Vd.clone())
+    sync()
+    Kr, _ = O.splice_kv(K_st, V_st, k_new, v_new, rows)
+    assert np.array_equal(to_host_bits(K2, "bf16"), np.ascontiguousarray(Kr).view(np.uint16))
+    L.close(), Ln.close()
+
+
+# ---------------------------------------------------------------------------
+# caller-supplied frequency table
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,pairing", [("C1", "half"), ("C2", "half"), ("C2", "interleaved")])
+def test_custom_frequency_table_on_the_gpu(cfg, pairing):
+    """inv_freq of the layer descriptor replaces the geometric table of Eq. (4) pair by pair, in the
+    re-rotation of cached keys and in the rotary embedding of fresh rows."""
+    spec = preset(cfg, chunk_lens=[90, 41, 130], m_prompt=8, pairing=pairing, permute_order=True)
+    half = spec.head_dim // 2
+    freqs = np.array([0.37 / (1 + j) + (0.011 if j % 3 == 0 else 0.0) + 0.002 * ((7 * j) % 5) for j in range(half)])
+    wl = make_workload(spec)
+    k, v, _ = oracle_inputs(wl)
+    L = make_layer(spec, max_ctx=wl.n_ctx, max_prompt=8, inv_freq=freqs.tolist())
+    kd, vd = dev_chunks(wl)
+    pos0 = [3, 0, 7]
+    K, V, starts, N = L.reposition_keys(kd, vd, chunk_order=wl.chunk_order.tolist(), cached_pos0=pos0)
+    sync()
+    K_ref, V_ref, start_ref, _ = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, pairing,
+                                                   cached_pos0=pos0, freqs=freqs)
+    assert starts == start_ref.tolist()
+    check_reposition(to_host_f64(K, spec.dtype), K_ref, spec.dtype, pairing)
+    # the default table gives something else entirely: the custom one was really used
+    K_def, _, _, _ = O.reposition_keys(k, v, wl.chunk_len, wl.chunk_order, spec.rope_theta, pairing, cached_pos0=pos0)
+    assert np.abs(to_host_f64(K, spec.dtype) - K_def).max() > 0.05 * np.abs(K_def).max()
+    g = np.random.Generator(np.random.Philox(key=[5, 5]))
+    x_st = to_storage(g.standard_normal((40, 3, spec.head_dim)) * 0.3, spec.dtype)
+    pos = np.sort(g.choice(140000, size=40, replace=False)).astype(np.int32)
+    xd = to_dev(x_st, spec.dtype)
+    L.rope_rows(xd, torch.from_numpy(pos).to(DEV))
+    sync()
+    check_reposition(to_host_f64(xd, spec.dtype), O.rope_rows(to_f64(x_st, spec.dtype), pos, spec.rope_theta, pairing, freqs=freqs),
+                     spec.dtype, pairing)
     L.close()
 
 
