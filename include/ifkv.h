@@ -196,6 +196,31 @@ int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx,
                       const void *k_prompt, int32_t accumulate, float *scores);
 
 /*
+ * Stages 1 and 2 in one call -- Eq. (5) and Eq. (7): ifkv_reposition_keys followed
+ * by ifkv_score_tokens on its k_out, with the same arguments, the same outputs
+ * (k_out, v_out, chunk_start_out, n_ctx_out, scores) and the same error
+ * behaviour as the two calls.  The scores need every re-rotated key twice (once
+ * for the softmax statistics of each prompt row, once for the column sums); given
+ * both stages at once the library may take the first of these sweeps straight
+ * from the chunk caches: a key is read once, advanced to its global rotary phase
+ * in registers, stored to k_out and multiplied with the prompt queries in the
+ * same kernel.  Either way k_out and v_out hold bit for bit what
+ * ifkv_reposition_keys writes and the scores are those of ifkv_score_tokens on
+ * that k_out.  Which way is taken is the library's choice (on the MI355X the two
+ * stages one after the other are faster at every measured shape, so that is the
+ * default; include/ifkv_debug.h has the knob).  Layer shapes the fused kernel
+ * does not serve (fp32, head_dim 64, IFKV_FLAG_FORCE_GENERIC, more than 512
+ * non-empty chunks, m_prompt = 0) always run the two stages.
+ */
+int ifkv_reposition_score(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_chunks,
+                          const void *const *v_chunks, const int32_t *chunk_len,
+                          const int32_t *chunk_order, const int32_t *cached_pos0,
+                          const int64_t *delta_override, void *k_out, void *v_out,
+                          int64_t *chunk_start_out, int64_t *n_ctx_out,
+                          const void *q_prompt, int32_t m_prompt, const void *k_prompt,
+                          int32_t accumulate, float *scores);
+
+/*
  * Stage 3 -- Eq. (8) with the budget k = floor(rho * N) of "Chunk Reordering":
  * one global top-k set, no per-chunk quota.
  *

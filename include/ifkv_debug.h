@@ -28,6 +28,12 @@ extern "C" {
  *   "attn_max_row_blocks"   stage 4: row blocks (128 query columns each) per
  *                           launch, 1 .. 65535; more rows take several
  *                           launches; 0 restores the default (65535)
+ *   "fused_repo_score"      ifkv_reposition_score: 1 = take the first scoring
+ *                           sweep straight from the chunk caches (one kernel
+ *                           re-rotates, stores and scores) where the layer
+ *                           shape allows; 0 (default) = the two stages one
+ *                           after the other, which is the faster of the two
+ *                           at every measured shape
  * A cut whose partial results would not fit the context's scratch (sized for
  * the largest launch the library cuts by itself) is not made.
  *

@@ -25,7 +25,7 @@ IFKV_FLAG_VALIDATE = 2
 
 EXPORTS = (
     "ifkv_create", "ifkv_destroy", "ifkv_last_error", "ifkv_version",
-    "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_select_topk", "ifkv_select_topk_noalloc",
+    "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_reposition_score", "ifkv_select_topk", "ifkv_select_topk_noalloc",
     "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
     "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",   # include/ifkv_calibrate.h
     "ifkv_set_tuning",                                                       # include/ifkv_debug.h
@@ -76,6 +76,10 @@ def load_library() -> C.CDLL:
     lib.ifkv_reposition_keys.restype = C.c_int
     lib.ifkv_score_tokens.argtypes = [vp, vp, i64, vp, i32, vp, i32, vp]
     lib.ifkv_score_tokens.restype = C.c_int
+    lib.ifkv_reposition_score.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32),
+                                          C.POINTER(i32), C.POINTER(i64), vp, vp, C.POINTER(i64), C.POINTER(i64),
+                                          vp, i32, vp, i32, vp]
+    lib.ifkv_reposition_score.restype = C.c_int
     lib.ifkv_select_topk.argtypes = [vp, vp, i64, C.c_double, i64, vp, C.POINTER(i64)]
     lib.ifkv_select_topk.restype = C.c_int
     lib.ifkv_select_topk_noalloc.argtypes = [vp, vp, i64, C.c_double, i64, vp, C.POINTER(i64)]
@@ -131,6 +135,7 @@ class Layer:
                  stream: Optional[int] = None, device: str = "cuda:0",
                  token_stride: int = 0, head_stride: int = 0):
         self._lib = load_library()
+        self._recording = None
         self.dtype = dtype
         self.torch_dtype = _TORCH_DTYPE[dtype]
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
@@ -173,6 +178,29 @@ class Layer:
         if rc != IFKV_OK:
             raise IfkvError(rc, self._lib.ifkv_last_error(self._ctx).decode())
 
+    def _invoke(self, cfunc, *cargs):
+        """One C call of a stage; while bind() records, the call is also kept for replay."""
+        if self._recording is not None:
+            self._recording.append((cfunc, cargs))
+        self._check(cfunc(*cargs))
+
+    def bind(self, stage: str, *args, **kw):
+        """Marshals a stage call once and returns a function that repeats it: stage(*args, **kw) runs
+        once now (checks, buffer look-ups, ctypes arrays), the returned function only re-issues the C
+        call(s) with the same arguments.  For loops that call a stage many times on the same buffers
+        (benchmarks, graph capture) without paying the Python-side marshalling every time."""
+        self._recording = []
+        try:
+            result = getattr(self, stage)(*args, **kw)
+        finally:
+            calls, self._recording = self._recording, None
+        check, keep = self._check, (args, kw, result)
+
+        def replay(_keep=keep):
+            for cfunc, cargs in calls:
+                check(cfunc(*cargs))
+        return replay
+
     def _empty(self, *shape, dtype=None):
         return torch.empty(*shape, dtype=dtype or self.torch_dtype, device=self.device)
 
@@ -207,12 +235,7 @@ class Layer:
         return t.data_ptr()
 
     # -- the five stages ------------------------------------------------------
-    def reposition_keys(self, k_chunks: List[torch.Tensor], v_chunks: Optional[List[torch.Tensor]] = None,
-                        chunk_order: Optional[Sequence[int]] = None,
-                        cached_pos0: Optional[Sequence[int]] = None,
-                        delta_override: Optional[Sequence[int]] = None,
-                        k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None
-                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor], List[int], int]:
+    def _repo_args(self, k_chunks, v_chunks, chunk_order, cached_pos0, delta_override, k_out, v_out):
         n = len(k_chunks)
         lens = [int(t.shape[0]) for t in k_chunks]
         N = sum(lens)
@@ -231,10 +254,38 @@ class Layer:
             raise ValueError("k_out / v_out: fewer rows than the chunks hold")
         starts = (C.c_int64 * max(n, 1))()
         n_ctx = C.c_int64()
-        self._check(self._lib.ifkv_reposition_keys(
-            self._ctx, n, kp, vp, _i32_array(lens), _i32_array(chunk_order), _i32_array(cached_pos0),
-            _i64_array(delta_override), self._cache(k_out, "k_out"), self._cache(v_out, "v_out"), starts, C.byref(n_ctx)))
+        args = (self._ctx, n, kp, vp, _i32_array(lens), _i32_array(chunk_order), _i32_array(cached_pos0),
+                _i64_array(delta_override), self._cache(k_out, "k_out"), self._cache(v_out, "v_out"), starts, C.byref(n_ctx))
+        return args, k_out, v_out, starts, n_ctx, n, N
+
+    def reposition_keys(self, k_chunks: List[torch.Tensor], v_chunks: Optional[List[torch.Tensor]] = None,
+                        chunk_order: Optional[Sequence[int]] = None,
+                        cached_pos0: Optional[Sequence[int]] = None,
+                        delta_override: Optional[Sequence[int]] = None,
+                        k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None
+                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor], List[int], int]:
+        args, k_out, v_out, starts, n_ctx, n, _ = self._repo_args(k_chunks, v_chunks, chunk_order, cached_pos0,
+                                                                   delta_override, k_out, v_out)
+        self._invoke(self._lib.ifkv_reposition_keys, *args)
         return k_out, v_out, [int(starts[i]) for i in range(n)], int(n_ctx.value)
+
+    def reposition_score(self, k_chunks: List[torch.Tensor], v_chunks: Optional[List[torch.Tensor]],
+                         q_prompt: torch.Tensor, chunk_order: Optional[Sequence[int]] = None,
+                         cached_pos0: Optional[Sequence[int]] = None, delta_override: Optional[Sequence[int]] = None,
+                         k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None,
+                         k_prompt: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                         accumulate: bool = False):
+        """ifkv_reposition_score: stages 1 and 2 in one call.  Returns (k_out, v_out, starts, n_ctx, scores)."""
+        args, k_out, v_out, starts, n_ctx, n, N = self._repo_args(k_chunks, v_chunks, chunk_order, cached_pos0,
+                                                                   delta_override, k_out, v_out)
+        m = int(q_prompt.shape[0])
+        if scores is None:
+            scores = self._empty(N, dtype=torch.float32)
+        self._invoke(self._lib.ifkv_reposition_score, 
+            *args, self._packed(q_prompt, "q_prompt", (self.n_q_heads, self.head_dim)), m,
+            self._packed(k_prompt, "k_prompt", (self.n_kv_heads, self.head_dim), rows=m), int(accumulate),
+            self._packed(scores, "scores", (), dtype=torch.float32, rows=N))
+        return k_out, v_out, [int(starts[i]) for i in range(n)], int(n_ctx.value), scores
 
     def score_tokens(self, k_global: torch.Tensor, q_prompt: torch.Tensor,
                      k_prompt: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
@@ -242,10 +293,10 @@ class Layer:
         n_ctx, m = int(k_global.shape[0]), int(q_prompt.shape[0])
         if scores is None:
             scores = self._empty(n_ctx, dtype=torch.float32)
-        self._check(self._lib.ifkv_score_tokens(
+        self._invoke(self._lib.ifkv_score_tokens, 
             self._ctx, self._cache(k_global, "k_global"), n_ctx, self._packed(q_prompt, "q_prompt", (self.n_q_heads, self.head_dim)), m,
             self._packed(k_prompt, "k_prompt", (self.n_kv_heads, self.head_dim), rows=m), int(accumulate),
-            self._packed(scores, "scores", (), dtype=torch.float32, rows=n_ctx)))
+            self._packed(scores, "scores", (), dtype=torch.float32, rows=n_ctx))
         return scores
 
     def select_topk(self, scores: torch.Tensor, ratio: float = 0.0, k: int = -1,
@@ -254,10 +305,10 @@ class Layer:
         k_out = C.c_int64()
         sp = self._packed(scores, "scores", (), dtype=torch.float32)
         if idx_out is None:   # the library knows the budget: ask it, then bring a buffer of that size
-            self._check(self._lib.ifkv_select_topk(self._ctx, sp, n_ctx, float(ratio), int(k), None, C.byref(k_out)))
+            self._invoke(self._lib.ifkv_select_topk, self._ctx, sp, n_ctx, float(ratio), int(k), None, C.byref(k_out))
             idx_out = self._empty(max(int(k_out.value), 1), dtype=torch.int32)
-        self._check(self._lib.ifkv_select_topk(self._ctx, sp, n_ctx, float(ratio), int(k),
-                                               self._packed(idx_out, "idx_out", (), dtype=torch.int32), C.byref(k_out)))
+        self._invoke(self._lib.ifkv_select_topk, self._ctx, sp, n_ctx, float(ratio), int(k),
+                                               self._packed(idx_out, "idx_out", (), dtype=torch.int32), C.byref(k_out))
         if idx_out.shape[0] < int(k_out.value):
             raise ValueError("idx_out: fewer entries than k")   # (checked by budget_of before the call in careful code)
         return idx_out[: int(k_out.value)]
@@ -265,15 +316,15 @@ class Layer:
     def budget_of(self, n_ctx: int, ratio: float = 0.0, k: int = -1) -> int:
         """k = floor(ratio * n_ctx) as the library evaluates it (no GPU work)."""
         k_out = C.c_int64()
-        self._check(self._lib.ifkv_select_topk(self._ctx, None, int(n_ctx), float(ratio), int(k), None, C.byref(k_out)))
+        self._invoke(self._lib.ifkv_select_topk, self._ctx, None, int(n_ctx), float(ratio), int(k), None, C.byref(k_out))
         return int(k_out.value)
 
     def select_topk_noalloc(self, scores: torch.Tensor, idx_out: torch.Tensor, ratio: float = 0.0, k: int = -1) -> torch.Tensor:
         """ifkv_select_topk_noalloc: the caller brings idx_out; the call allocates nothing."""
         k_out = C.c_int64()
-        self._check(self._lib.ifkv_select_topk_noalloc(self._ctx, self._packed(scores, "scores", (), dtype=torch.float32),
+        self._invoke(self._lib.ifkv_select_topk_noalloc, self._ctx, self._packed(scores, "scores", (), dtype=torch.float32),
                                                        int(scores.shape[0]), float(ratio), int(k),
-                                                       self._packed(idx_out, "idx_out", (), dtype=torch.int32), C.byref(k_out)))
+                                                       self._packed(idx_out, "idx_out", (), dtype=torch.int32), C.byref(k_out))
         return idx_out[: int(k_out.value)]
 
     def recompute_attention(self, q_sel: torch.Tensor, row_pos: torch.Tensor, k_cache: torch.Tensor,
@@ -284,28 +335,28 @@ class Layer:
             out = self._empty(n_rows, self.n_q_heads, self.head_dim)
         lse = self._empty(n_rows, self.n_q_heads, dtype=torch.float32) if return_lse else None
         qh = (self.n_q_heads, self.head_dim)
-        self._check(self._lib.ifkv_recompute_attention(
+        self._invoke(self._lib.ifkv_recompute_attention, 
             self._ctx, self._packed(q_sel, "q_sel", qh), self._packed(row_pos, "row_pos", (), dtype=torch.int32, rows=n_rows), n_rows,
             self._cache(k_cache, "k_cache"), self._cache(v_cache, "v_cache"), n_kv, self._packed(out, "out", qh, rows=n_rows),
-            self._packed(lse, "lse", (self.n_q_heads,), dtype=torch.float32, rows=n_rows)))
+            self._packed(lse, "lse", (self.n_q_heads,), dtype=torch.float32, rows=n_rows))
         return (out, lse) if return_lse else out
 
     def splice_kv(self, k_new: torch.Tensor, v_new: Optional[torch.Tensor], idx: torch.Tensor,
                   k_cache: torch.Tensor, v_cache: Optional[torch.Tensor]) -> None:
         n = int(idx.shape[0])
         kv_tail = (self.n_kv_heads, self.head_dim)
-        self._check(self._lib.ifkv_splice_kv(self._ctx, self._packed(k_new, "k_new", kv_tail, rows=n),
+        self._invoke(self._lib.ifkv_splice_kv, self._ctx, self._packed(k_new, "k_new", kv_tail, rows=n),
                                              self._packed(v_new, "v_new", kv_tail, rows=n),
                                              self._packed(idx, "idx", (), dtype=torch.int32), n,
-                                             self._cache(k_cache, "k_cache"), self._cache(v_cache, "v_cache"), int(k_cache.shape[0])))
+                                             self._cache(k_cache, "k_cache"), self._cache(v_cache, "v_cache"), int(k_cache.shape[0]))
 
     def rope_rows(self, x: torch.Tensor, pos: torch.Tensor) -> torch.Tensor:
         """In place; x [R, n_heads, d], pos int32 [R]."""
         if x.dim() != 3 or x.shape[2] != self.head_dim:
             raise ValueError(f"x: expected [R, n_heads, {self.head_dim}], got {tuple(x.shape)}")
-        self._check(self._lib.ifkv_rope_rows(self._ctx, self._packed(x, "x", tuple(x.shape[1:])),
+        self._invoke(self._lib.ifkv_rope_rows, self._ctx, self._packed(x, "x", tuple(x.shape[1:])),
                                              self._packed(pos, "pos", (), dtype=torch.int32, rows=int(x.shape[0])),
-                                             int(x.shape[0]), int(x.shape[1])))
+                                             int(x.shape[0]), int(x.shape[1]))
         return x
 
     def chunk_counts(self, idx: torch.Tensor, slot_start: Sequence[int], n_ctx: int,
@@ -313,9 +364,9 @@ class Layer:
         n_slots = len(slot_start)
         if counts_out is None:
             counts_out = self._empty(max(n_slots, 1), dtype=torch.int32)
-        self._check(self._lib.ifkv_chunk_counts(self._ctx, self._packed(idx, "idx", (), dtype=torch.int32), int(idx.shape[0]), n_slots,
+        self._invoke(self._lib.ifkv_chunk_counts, self._ctx, self._packed(idx, "idx", (), dtype=torch.int32), int(idx.shape[0]), n_slots,
                                                 _i64_array(slot_start), int(n_ctx),
-                                                self._packed(counts_out, "counts_out", (), dtype=torch.int32, rows=n_slots)))
+                                                self._packed(counts_out, "counts_out", (), dtype=torch.int32, rows=n_slots))
         return counts_out[:n_slots]
 
     def reorder_chunks(self, order_in: Optional[Sequence[int]], slot_counts: Sequence[int],

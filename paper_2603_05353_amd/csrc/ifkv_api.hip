@@ -12,6 +12,7 @@
 #include "ifkv_calibrate.h"
 #include "ifkv_debug.h"
 #include "ifkv_internal.h"
+#include "score_common.h"
 
 namespace {
 
@@ -152,18 +153,35 @@ void ifkv_destroy(ifkv_ctx *ctx) {
   delete ctx;
 }
 
-int ifkv_reposition_keys(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_chunks,
-                         const void *const *v_chunks, const int32_t *chunk_len,
-                         const int32_t *chunk_order, const int32_t *cached_pos0,
-                         const int64_t *delta_override, void *k_out, void *v_out,
-                         int64_t *chunk_start_out, int64_t *n_ctx_out) {
-  if (ctx == nullptr) return IFKV_EINVAL;
+namespace {
+
+struct RepoArgs {
+  int32_t n_chunks;
+  const void *const *k_chunks;
+  const void *const *v_chunks;
+  const int32_t *chunk_len;
+  const int32_t *chunk_order;
+  const int32_t *cached_pos0;
+  const int64_t *delta_override;
+  void *k_out, *v_out;
+  int64_t *chunk_start_out, *n_ctx_out;
+};
+
+// Stage 1, host part: argument checks, Eq. (5) (start of every chunk in the concatenation order) and
+// the host outputs.  `start` gets the first row of every chunk, *n_ctx_p the number of rows.
+int repo_validate(ifkv_ctx *ctx, const RepoArgs &a, std::vector<int64_t> &start, int64_t *n_ctx_p) {
+  const int32_t n_chunks = a.n_chunks;
+  const void *const *k_chunks = a.k_chunks;
+  const void *const *v_chunks = a.v_chunks;
+  const int32_t *chunk_len = a.chunk_len, *chunk_order = a.chunk_order;
+  void *k_out = a.k_out, *v_out = a.v_out;
+  int64_t *chunk_start_out = a.chunk_start_out, *n_ctx_out = a.n_ctx_out;
   if (n_chunks < 0) return fail(ctx, IFKV_EINVAL, "reposition_keys: n_chunks=%d is negative", n_chunks);
   if (n_chunks > 0 && (k_chunks == nullptr || chunk_len == nullptr))
     return fail(ctx, IFKV_EINVAL, "reposition_keys: k_chunks and chunk_len are required");
 
   // Eq. (5): start of every chunk in the concatenation order
-  std::vector<int64_t> start(n_chunks, 0);
+  start.assign(n_chunks > 0 ? n_chunks : 0, 0);
   std::vector<char> seen(n_chunks, 0);
   int64_t n_ctx = 0;
   for (int s = 0; s < n_chunks; ++s) {
@@ -196,8 +214,23 @@ int ifkv_reposition_keys(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_c
   if (chunk_start_out != nullptr)
     for (int c = 0; c < n_chunks; ++c) chunk_start_out[c] = start[c];
   if (n_ctx_out != nullptr) *n_ctx_out = n_ctx;
-  if (n_ctx == 0) return IFKV_OK;
+  *n_ctx_p = n_ctx;
+  return IFKV_OK;
 
+}
+
+int64_t repo_advance(const RepoArgs &a, const std::vector<int64_t> &start, int c) {
+  return a.delta_override != nullptr ? a.delta_override[c]
+                                     : start[c] - (a.cached_pos0 != nullptr ? static_cast<int64_t>(a.cached_pos0[c]) : 0);
+}
+
+// Stage 1, device part (the stage on its own).
+int repo_launch(ifkv_ctx *ctx, const RepoArgs &a, const std::vector<int64_t> &start) {
+  const int32_t n_chunks = a.n_chunks;
+  const void *const *k_chunks = a.k_chunks;
+  const void *const *v_chunks = a.v_chunks;
+  const int32_t *chunk_len = a.chunk_len;
+  void *k_out = a.k_out, *v_out = a.v_out;
   int rc = ensure_inv_freq(ctx);
   if (rc != IFKV_OK) return rc;
 
@@ -218,9 +251,7 @@ int ifkv_reposition_keys(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_c
     rc_.k = k_chunks[c];
     rc_.v = v_chunks != nullptr ? v_chunks[c] : nullptr;
     rc_.dst_row = start[c];
-    const int64_t adv = delta_override != nullptr
-                            ? delta_override[c]
-                            : start[c] - (cached_pos0 != nullptr ? static_cast<int64_t>(cached_pos0[c]) : 0);
+    const int64_t adv = repo_advance(a, start, c);
     rc_.advance = static_cast<double>(adv);
     rc_.len = chunk_len[c];
     rc_.tile0 = batch.total_tiles;
@@ -233,9 +264,8 @@ int ifkv_reposition_keys(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_c
   return flush();
 }
 
-int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
-                      int32_t m_prompt, const void *k_prompt, int32_t accumulate, float *scores) {
-  if (ctx == nullptr) return IFKV_EINVAL;
+int score_validate(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt, int32_t m_prompt,
+                   const void *k_prompt, const float *scores) {
   if (n_ctx < 0 || m_prompt < 0) return fail(ctx, IFKV_EINVAL, "score_tokens: negative size");
   if (n_ctx > ctx->desc.max_ctx)
     return fail(ctx, IFKV_ESHAPE, "score_tokens: n_ctx=%lld exceeds max_ctx=%lld", static_cast<long long>(n_ctx),
@@ -248,7 +278,70 @@ int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const 
     return fail(ctx, IFKV_EINVAL, "score_tokens: k_global and q_prompt are required");
   if (!aligned16(k_global) || !aligned16(q_prompt) || !aligned16(k_prompt))
     return fail(ctx, IFKV_EINVAL, "score_tokens: inputs must be 16-byte aligned");
-  int rc = ensure_scratch(ctx);
+  return IFKV_OK;
+}
+
+}  // namespace
+
+int ifkv_reposition_keys(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_chunks,
+                         const void *const *v_chunks, const int32_t *chunk_len,
+                         const int32_t *chunk_order, const int32_t *cached_pos0,
+                         const int64_t *delta_override, void *k_out, void *v_out,
+                         int64_t *chunk_start_out, int64_t *n_ctx_out) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  const RepoArgs a = {n_chunks, k_chunks, v_chunks, chunk_len, chunk_order, cached_pos0, delta_override,
+                      k_out, v_out, chunk_start_out, n_ctx_out};
+  std::vector<int64_t> start;
+  int64_t n_ctx = 0;
+  int rc = repo_validate(ctx, a, start, &n_ctx);
+  if (rc != IFKV_OK || n_ctx == 0) return rc;
+  return repo_launch(ctx, a, start);
+}
+
+int ifkv_reposition_score(ifkv_ctx *ctx, int32_t n_chunks, const void *const *k_chunks,
+                          const void *const *v_chunks, const int32_t *chunk_len, const int32_t *chunk_order,
+                          const int32_t *cached_pos0, const int64_t *delta_override, void *k_out, void *v_out,
+                          int64_t *chunk_start_out, int64_t *n_ctx_out, const void *q_prompt, int32_t m_prompt,
+                          const void *k_prompt, int32_t accumulate, float *scores) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  const RepoArgs a = {n_chunks, k_chunks, v_chunks, chunk_len, chunk_order, cached_pos0, delta_override,
+                      k_out, v_out, chunk_start_out, n_ctx_out};
+  std::vector<int64_t> start;
+  int64_t n_ctx = 0;
+  int rc = repo_validate(ctx, a, start, &n_ctx);
+  if (rc != IFKV_OK) return rc;
+  rc = score_validate(ctx, k_out, n_ctx, q_prompt, m_prompt, k_prompt, scores);
+  if (rc != IFKV_OK || n_ctx == 0) return rc;
+  rc = ensure_scratch(ctx);
+  if (rc != IFKV_OK) return rc;
+  // chunks that hold rows, in the order of the concatenation
+  std::vector<ifkv::FusedHostChunk> fc;
+  for (int s = 0; s < n_chunks; ++s) {
+    const int c = chunk_order != nullptr ? chunk_order[s] : s;
+    if (chunk_len[c] == 0) continue;
+    fc.push_back({k_chunks[c], v_chunks != nullptr ? v_chunks[c] : nullptr, start[c],
+                  static_cast<double>(repo_advance(a, start, c))});
+  }
+  if (m_prompt > 0 && ifkv::fused_repo_score_supported(ctx, m_prompt, static_cast<int>(fc.size()))) {
+    rc = ensure_inv_freq(ctx);
+    if (rc != IFKV_OK) return rc;
+    const ifkv::FusedRepo fr = {fc.data(), static_cast<int>(fc.size()), k_out, v_chunks != nullptr ? v_out : nullptr};
+    hipError_t e = ifkv::launch_score(ctx, k_out, n_ctx, q_prompt, m_prompt, k_prompt, accumulate != 0, scores, &fr);
+    return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "fused reposition + score launch");
+  }
+  // otherwise the two stages one after the other
+  rc = repo_launch(ctx, a, start);
+  if (rc != IFKV_OK) return rc;
+  hipError_t e = ifkv::launch_score(ctx, k_out, n_ctx, q_prompt, m_prompt, k_prompt, accumulate != 0, scores);
+  return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "score kernel launch");
+}
+
+int ifkv_score_tokens(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
+                      int32_t m_prompt, const void *k_prompt, int32_t accumulate, float *scores) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  int rc = score_validate(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, scores);
+  if (rc != IFKV_OK || n_ctx == 0) return rc;
+  rc = ensure_scratch(ctx);
   if (rc != IFKV_OK) return rc;
   hipError_t e = ifkv::launch_score(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate != 0, scores);
   return e == hipSuccess ? IFKV_OK : hip_fail(ctx, e, "score kernel launch");
@@ -445,7 +538,8 @@ int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value) {
     int64_t hi;
   } knobs[] = {{"attn_split_parts", &ctx->tune.attn_split_parts, 65535},
                {"attn_part_tiles", &ctx->tune.attn_part_tiles, 1 << 24},
-               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 65535}};
+               {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 65535},
+               {"fused_repo_score", &ctx->tune.fused_repo_score, 1}};
   for (const Knob &k : knobs) {
     if (std::strcmp(key, k.name) != 0) continue;
     if (value < 0 || value > k.hi)

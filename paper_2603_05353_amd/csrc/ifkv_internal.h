@@ -14,6 +14,7 @@ struct ifkv_tuning {
   int attn_split_parts = 0;      // stage 4: cut the kv axis into this many equal parts
   int attn_part_tiles = 0;       // stage 4: cut the kv axis into parts of this many tiles (takes precedence)
   int attn_max_row_blocks = 0;   // stage 4: row blocks per launch (can only lower the default)
+  int fused_repo_score = 0;      // stages 1+2 in one call: 1 = take the first scoring sweep from the chunk caches
 };
 
 struct ifkv_ctx {
@@ -67,8 +68,10 @@ int reposition_rows_per_tile();
 
 // Stage 2.
 size_t score_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt);
+struct FusedRepo;  // score_common.h: stage 1 folded into the first scoring sweep
 hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
-                        int m_prompt, const void *k_prompt, int accumulate, float *scores);
+                        int m_prompt, const void *k_prompt, int accumulate, float *scores,
+                        const FusedRepo *fused = nullptr);
 
 // Stage 3.
 size_t topk_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx);

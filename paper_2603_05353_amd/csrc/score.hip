@@ -230,7 +230,8 @@ ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prom
   const int64_t max_slices = 256;  // upper bound for both the ALU and the MFMA partition
   s.stats_off = 0;
   s.partial_off = ((rows * sizeof(float2) + 255) / 256) * 256;
-  s.colpart_off = s.partial_off + ((max_slices * rows * sizeof(float2) + 255) / 256) * 256;
+  s.fused_off = s.partial_off + ((max_slices * rows * sizeof(float2) + 255) / 256) * 256;
+  s.colpart_off = s.fused_off + ((kFusedTableBytes + 255) / 256) * 256;
   // per-(kv head, query chunk) partial column sums of the MFMA pass B
   const int64_t parts = static_cast<int64_t>(d.n_kv_heads) * kMaxQChunks;
   s.total = s.colpart_off + static_cast<size_t>(parts) * static_cast<size_t>(n_ctx > 0 ? n_ctx : 1) * sizeof(float);
@@ -242,7 +243,7 @@ size_t score_scratch_bytes(const ifkv_ctx *ctx, int64_t n_ctx, int m_prompt) {
 }
 
 hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt, int m_prompt,
-                        const void *k_prompt, int accumulate, float *scores) {
+                        const void *k_prompt, int accumulate, float *scores, const FusedRepo *fused) {
   if (n_ctx <= 0) return hipSuccess;
   const auto &d = ctx->desc;
   if (m_prompt <= 0) {
@@ -256,7 +257,7 @@ hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, cons
   if (!generic) {
     // MFMA sweeps around the same merge kernel (which also folds in the prompt keys)
     int n_slices = 0;
-    hipError_t e = launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, false, 0, nullptr);
+    hipError_t e = launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, false, 0, nullptr, fused);
     if (e != hipSuccess) return e;
     ScoreScratch sc = score_scratch_layout(ctx, n_ctx, m_prompt);
     float2 *partial = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.partial_off);

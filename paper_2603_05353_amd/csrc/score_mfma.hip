@@ -16,6 +16,7 @@
 //           blocks at the end.
 //   pass B: S = Q.K^T, a lane owns one key -> sum over query rows of
 //           exp2(S*c - b_q) with b_q = log2-domain max + log2 Z, in-lane.
+#include <algorithm>
 #include <type_traits>
 
 #include "ifkv_device.h"
@@ -108,6 +109,145 @@ __device__ __forceinline__ void load_k_frags(bf16x8 (&kf)[2][8], const uint16_t 
   }
 }
 
+// ---------------------------------------------------------------------------
+// Fused stage 1 + pass A -- Eq. (5) and Eq. (7) in one sweep: the key fragments come from the chunk
+// caches instead of the concatenated cache, are advanced to their global rotary phase in
+// registers, rounded to bf16 once (exactly the values stage 1 stores), written to the
+// concatenated cache by the blocks of query chunk 0, and fed to the MFMAs.  A lane holds, for each
+// of its two keys, columns 16 s + 8 hf .. +7 (s = 0..7): both halves of every (x_i, x_{i+64}) pair
+// and every (x_{2i}, x_{2i+1}) pair it touches, so the rotation needs no other lane.  The value
+// rows of the same keys are copied along (stage 1 moves them too).
+// Measured at 32K context (64 chunks of 512 rows, prompt lengths 1 .. 256): the fused sweep is 20 to
+// 50 us slower than the two stages one after the other.  A kernel shaped for the matrix pipes (eight
+// wavefronts per compute unit, a few dozen loads in flight each, two key tiles per wavefront) keeps
+// about 0.5 MB in flight over the whole chip, where streaming 256 MB at the rate of stage 1's own
+// kernel takes some 10 MB; the streaming does not hide under the matrix work, it stretches it.  The
+// library therefore runs the two stages separately unless the fused sweep is asked for by the
+// tuning knob "fused_repo_score" (which the tests use to keep this path checked).
+// ---------------------------------------------------------------------------
+struct FusedChunk {      // one non-empty chunk, in the order of the concatenation
+  const uint16_t *k;     // [len, H_kv, 128] packed
+  const uint16_t *v;     // same shape, or null
+  int32_t dst_row;       // first row in the concatenated cache
+  int32_t rotate;        // 0: phase advance is zero, the rows are copied bit for bit
+};
+struct FusedArgs {
+  const FusedChunk *chunks;  // device, [n_chunks]
+  const int32_t *starts;     // device, [n_chunks]: dst_row of every chunk, ascending
+  const float *rot;          // device, [n_chunks][128]: per half-wave 64 floats, see fused_table_kernel
+  uint16_t *k_out, *v_out;   // concatenated caches (v_out may be null)
+  int32_t n_chunks;
+  int32_t pairing;
+};
+constexpr int kMaxFusedChunks = 512;
+
+// (cos, sin) of a chunk's phase advance in the order a lane consumes them: for lane half hf the 64
+// floats at rot[c * 128 + hf * 64 ..].  Half-split pairs: [s = 0..3][cos of frequencies
+// 16 s + 8 hf + 0..7, then their sines].  Interleaved pairs: [s = 0..7][cos of pairs
+// 8 s + 4 hf + 0..3, then their sines].  Angles in fp64 (positions reach 1e5), stored as fp32: the
+// same values stage 1's own kernel uses.
+struct FusedTableBatch {
+  FusedChunk c[64];
+  double advance[64];
+  int32_t n, base;
+};
+__global__ __launch_bounds__(64) void fused_table_kernel(FusedTableBatch b, const double *__restrict__ inv_freq,
+                                                         FusedChunk *__restrict__ chunks, int32_t *__restrict__ starts,
+                                                         float *__restrict__ rot, int pairing) {
+  const int i = blockIdx.x, f = threadIdx.x;
+  const int c = b.base + i;
+  if (f == 0) {
+    chunks[c] = b.c[i];
+    starts[c] = b.c[i].dst_row;
+  }
+  double sn, cs;
+  sincos(b.advance[i] * inv_freq[f], &sn, &cs);
+  int at;
+  if (pairing == IFKV_ROPE_HALF)
+    at = ((f >> 3) & 1) * 64 + (f >> 4) * 16 + (f & 7);
+  else
+    at = ((f >> 2) & 1) * 64 + (f >> 3) * 8 + (f & 3);
+  const int to_sin = pairing == IFKV_ROPE_HALF ? 8 : 4;
+  rot[c * 128 + at] = static_cast<float>(cs);
+  rot[c * 128 + at + to_sin] = static_cast<float>(sn);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
+  return float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16);
+}
+
+// The fused counterpart of load_k_frags for keys j0 .. j0+63 (lane (row, hf): keys j0 + row and
+// j0 + 32 + row); s_starts: the chunks' first rows in LDS.
+__device__ __forceinline__ void fused_k_frags(bf16x8 (&kf)[2][8], const FusedArgs &fa, const int32_t *s_starts,
+                                              const ScoreGeom &gm, int g, int j0, int row, int hf, bool store) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int j_real = j0 + 32 * t + row;
+    const int j = min(j_real, gm.n_ctx - 1);
+    int lo = 0, hi = fa.n_chunks;  // s_starts[lo] <= j < s_starts[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (s_starts[mid] <= j) lo = mid; else hi = mid;
+    }
+    const FusedChunk ch = fa.chunks[lo];
+    const int64_t src = (static_cast<int64_t>(j - ch.dst_row) * gm.n_kv_heads + g) * D + 8 * hf;
+    const int64_t dst = static_cast<int64_t>(j) * gm.token_stride + g * gm.head_stride + 8 * hf;
+    const bool write = store && j_real < gm.n_ctx;
+    v4u x[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) x[s] = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(ch.k + src + 16 * s));
+    if (ch.v != nullptr && fa.v_out != nullptr && write) {
+      v4u y[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) y[s] = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(ch.v + src + 16 * s));
+#pragma unroll
+      for (int s = 0; s < 8; ++s) __builtin_nontemporal_store(y[s], reinterpret_cast<v4u *>(fa.v_out + dst + 16 * s));
+    }
+    if (ch.rotate != 0) {
+      const float4 *tb = reinterpret_cast<const float4 *>(fa.rot + lo * 128 + hf * 64);
+      if (fa.pairing == IFKV_ROPE_HALF) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const float4 c0 = tb[4 * s], c1 = tb[4 * s + 1], s0 = tb[4 * s + 2], s1 = tb[4 * s + 3];
+          const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+          const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+          float a[8], b[8], ra[8], rb[8];
+          Elem<BF16Tag>::unpack(x[s], a);
+          Elem<BF16Tag>::unpack(x[s + 4], b);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            ra[e] = fmaf(a[e], cs[e], -(b[e] * sn[e]));
+            rb[e] = fmaf(a[e], sn[e], b[e] * cs[e]);
+          }
+          x[s] = Elem<BF16Tag>::pack(ra);
+          x[s + 4] = Elem<BF16Tag>::pack(rb);
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const float4 c0 = tb[2 * s], s0 = tb[2 * s + 1];
+          const float cs[4] = {c0.x, c0.y, c0.z, c0.w};
+          const float sn[4] = {s0.x, s0.y, s0.z, s0.w};
+          float f[8], r[8];
+          Elem<BF16Tag>::unpack(x[s], f);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            r[2 * e] = fmaf(f[2 * e], cs[e], -(f[2 * e + 1] * sn[e]));
+            r[2 * e + 1] = fmaf(f[2 * e], sn[e], f[2 * e + 1] * cs[e]);
+          }
+          x[s] = Elem<BF16Tag>::pack(r);
+        }
+      }
+    }
+    if (write) {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) __builtin_nontemporal_store(x[s], reinterpret_cast<v4u *>(fa.k_out + dst + 16 * s));
+    }
+#pragma unroll
+    for (int s = 0; s < 8; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, x[s]);
+  }
+}
+
 // Query fragment s of 32-row block qb: lane (row, hf) holds columns 16 s + 8 hf .. +7 of row qb*32 + row.
 __device__ __forceinline__ bf16x8 q_frag(const uint16_t *q_lds, int qb, int s, int row, int hf) {
   return __builtin_bit_cast(bf16x8,
@@ -155,11 +295,13 @@ __device__ __forceinline__ void qk_block(f32x16 &S0, f32x16 &S1, const bf16x8 (&
 // order instructions only within a basic block.  With a run-time block count the compiler hoisted
 // all MFMAs of a tile above the vector work of its first block and moved the vector work of one
 // step behind the MFMAs of the next.
-template <int NQB>
+// FUSED: the keys come from the chunk caches through fused_k_frags (k_global is not read).
+template <int NQB, bool FUSED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, kWpe))) void score_stats_mfma(
     const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm,
-    float2 *__restrict__ partial) {
+    float2 *__restrict__ partial, FusedArgs fa) {
   __shared__ __attribute__((aligned(16))) uint16_t q_lds[NQB * 32 * QSTR];
+  __shared__ int32_t s_starts[FUSED ? kMaxFusedChunks : 1];
   const int kb = blockIdx.x;
   const int g = blockIdx.y / gm.n_qchunks;
   const int qc = blockIdx.y - g * gm.n_qchunks;
@@ -171,13 +313,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
   const float c = gm.scale_log2;
   const int kv_begin = kb * gm.kv_per_block;
   const int kv_end = min(gm.n_ctx, kv_begin + gm.kv_per_block);
+  if (FUSED) {  // the chunks' first rows, searched by every lane for its keys
+    for (int i = threadIdx.x; i < fa.n_chunks; i += kThreads) s_starts[i] = fa.starts[i];
+    __syncthreads();
+  }
+  auto next_keys = [&](bf16x8 (&dst)[2][8], int j) {
+    if (FUSED)
+      fused_k_frags(dst, fa, s_starts, gm, g, j, row, hf, qc == 0);
+    else
+      load_k_frags(dst, k_global, gm, g, j, row, hf);
+  };
   // the query tile and the first key tile are requested together, before anything waits
   bf16x8 kf[2][8];
   int j0 = kv_begin + wave * kTile;
   {
     v4u qx[NQB];
     q_tile_request<NQB>(qx, q_prompt, gm, g, qc);
-    if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
+    if (j0 < kv_end) next_keys(kf, j0);
     q_tile_store<NQB>(q_lds, qx);
   }
   __syncthreads();
@@ -270,7 +422,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
     else
       tile(std::false_type{}, j0);
     const int j_next = j0 + kWaves * kTile;
-    if (j_next < kv_end) load_k_frags(kf, k_global, gm, g, j_next, row, hf);
+    if (j_next < kv_end) next_keys(kf, j_next);
   }
 
   // merge the two lane halves (same query row, disjoint keys), then the wavefronts
@@ -445,8 +597,16 @@ bool score_mfma_supported(const ifkv_ctx *ctx, int m_prompt) {
          static_cast<int64_t>(m_prompt) * G <= static_cast<int64_t>(kMaxQChunks) * kQChunk;
 }
 
+bool fused_repo_score_supported(const ifkv_ctx *ctx, int m_prompt, int n_chunks) {
+  return ctx->tune.fused_repo_score != 0 && !(ctx->desc.flags & IFKV_FLAG_FORCE_GENERIC) && score_mfma_supported(ctx, m_prompt) && n_chunks >= 1 &&
+         n_chunks <= kFusedMaxChunks;
+}
+
 hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
-                                    int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores) {
+                                    int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores,
+                                    const FusedRepo *fused) {
+  static_assert(kMaxFusedChunks == kFusedMaxChunks, "one limit");
+  static_assert(sizeof(FusedChunk) <= 32, "descriptor slot");
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
   ScoreGeom gm;
@@ -482,12 +642,51 @@ hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t
   if (!pass_b) {
     const auto *kg = static_cast<const uint16_t *>(k_global);
     const auto *qp = static_cast<const uint16_t *>(q_prompt);
-    switch (gm.q_chunk_rows / 128) {
-      case 1: hipLaunchKernelGGL(score_stats_mfma<4>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
-      case 2: hipLaunchKernelGGL(score_stats_mfma<8>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
-      case 3: hipLaunchKernelGGL(score_stats_mfma<12>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
-      default: hipLaunchKernelGGL(score_stats_mfma<16>, grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial); break;
+    FusedArgs fa = {};
+    if (fused != nullptr) {
+      // the chunk table, the first rows and the rotation table reach the device through the
+      // arguments of small kernels (64 chunks each): no staging copy, no host sync
+      char *fb = base + sc.fused_off;
+      FusedChunk *d_chunks = reinterpret_cast<FusedChunk *>(fb);
+      int32_t *d_starts = reinterpret_cast<int32_t *>(fb + kFusedMaxChunks * 32);
+      float *d_rot = reinterpret_cast<float *>(fb + kFusedMaxChunks * 36);
+      for (int b0 = 0; b0 < fused->n_chunks; b0 += 64) {
+        FusedTableBatch tb;
+        tb.n = std::min(64, fused->n_chunks - b0);
+        tb.base = b0;
+        for (int i = 0; i < tb.n; ++i) {
+          const FusedHostChunk &hc = fused->chunks[b0 + i];
+          tb.c[i].k = static_cast<const uint16_t *>(hc.k);
+          tb.c[i].v = static_cast<const uint16_t *>(hc.v);
+          tb.c[i].dst_row = static_cast<int32_t>(hc.dst_row);
+          tb.c[i].rotate = hc.advance != 0.0 ? 1 : 0;
+          tb.advance[i] = hc.advance;
+        }
+        hipLaunchKernelGGL(fused_table_kernel, dim3(tb.n), dim3(64), 0, ctx->stream, tb, ctx->d_inv_freq, d_chunks,
+                           d_starts, d_rot, static_cast<int>(d.pairing));
+      }
+      fa.chunks = d_chunks;
+      fa.starts = d_starts;
+      fa.rot = d_rot;
+      fa.k_out = static_cast<uint16_t *>(fused->k_out);
+      fa.v_out = static_cast<uint16_t *>(fused->v_out);
+      fa.n_chunks = fused->n_chunks;
+      fa.pairing = d.pairing;
     }
+#define IFKV_LAUNCH_STATS(NQB)                                                                                          \
+  do {                                                                                                                  \
+    if (fused != nullptr)                                                                                               \
+      hipLaunchKernelGGL((score_stats_mfma<NQB, true>), grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial, fa); \
+    else                                                                                                                \
+      hipLaunchKernelGGL((score_stats_mfma<NQB, false>), grid, dim3(kThreads), 0, ctx->stream, kg, qp, gm, partial, fa); \
+  } while (0)
+    switch (gm.q_chunk_rows / 128) {
+      case 1: IFKV_LAUNCH_STATS(4); break;
+      case 2: IFKV_LAUNCH_STATS(8); break;
+      case 3: IFKV_LAUNCH_STATS(12); break;
+      default: IFKV_LAUNCH_STATS(16); break;
+    }
+#undef IFKV_LAUNCH_STATS
   } else {
     hipLaunchKernelGGL(score_colsum_mfma, grid, dim3(kThreads), 0, ctx->stream,
                        static_cast<const uint16_t *>(k_global), static_cast<const uint16_t *>(q_prompt), gm, stats,

@@ -216,7 +216,9 @@ def test_set_tuning_validation(lib):
     L.set_tuning("attn_part_tiles", 40)
     L.set_tuning("attn_max_row_blocks", 2)
     L.set_tuning("attn_part_tiles", 0)
-    for key, value in [("attn_split_parts", 65536), ("attn_split_parts", -1), ("attn_max_row_blocks", 65536),
+    L.set_tuning("fused_repo_score", 1)
+    L.set_tuning("fused_repo_score", 0)
+    for key, value in [("attn_split_parts", 65536), ("attn_split_parts", -1), ("attn_max_row_blocks", 65536), ("fused_repo_score", 2),
                        ("no_such_knob", 1)]:
         with pytest.raises(B.IfkvError) as e:
             L.set_tuning(key, value)

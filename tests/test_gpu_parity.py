@@ -239,6 +239,86 @@ def test_score_peaky_logits():
 
 
 # ---------------------------------------------------------------------------
+# stages 1 + 2 in one call (the first scoring sweep reads the chunk caches)
+# ---------------------------------------------------------------------------
+FUSED_CASES = [
+    # name, spec, extras
+    ("C2-permuted", preset("C2", chunk_lens=[256, 100, 190, 64, 333], m_prompt=32, permute_order=True), {}),
+    ("ragged-with-empty-chunk", preset("C2", chunk_lens=[70, 0, 33, 129, 16, 1, 400], m_prompt=19, permute_order=True), {}),
+    ("one-prompt-row", preset("C2", chunk_lens=[300, 211], m_prompt=1), {}),
+    ("8-prompt-rows", preset("C3", chunk_lens=[130] * 9, m_prompt=8), {}),
+    ("two-query-chunks", preset("C2", chunk_lens=[600, 424], m_prompt=160), {}),                  # 640 query rows per kv head
+    ("more-than-64-chunks", preset("C3", chunk_lens=[5] * 70 + [17] * 3 + [240], m_prompt=12), {}),
+    ("C5-gqa7", preset("C5", chunk_lens=[200] * 4 + [96] * 3, m_prompt=24), {}),
+    ("interleaved", preset("C2", chunk_lens=[150, 31, 264], m_prompt=16, pairing="interleaved", permute_order=True), {}),
+    ("cached-from-other-positions", preset("C2", chunk_lens=[90, 141, 130], m_prompt=16), {"cached_pos0": [3, 0, 7]}),
+    ("local-geometry", preset("C2", chunk_lens=[90, 141, 130], m_prompt=16), {"delta_override": [0, 0, 0]}),
+    ("prompt-keys", preset("C2", chunk_lens=[256, 100, 190], m_prompt=24, permute_order=True), {"with_k_prompt": True}),
+    ("keys-only", preset("C2", chunk_lens=[256, 100, 190], m_prompt=24), {"no_v": True}),
+    ("head-major-cache", preset("C2", chunk_lens=[256, 100, 190], m_prompt=24, permute_order=True), {"layout": "head-major"}),
+    ("fp32-falls-back", preset("C1", chunk_lens=[100, 61, 130], m_prompt=12), {}),
+    ("alu-falls-back", preset("C2", chunk_lens=[120, 77], m_prompt=9), {"flags": FORCE_GENERIC}),
+]
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused-sweep", "two-stages"])
+@pytest.mark.parametrize("name,spec,extra", FUSED_CASES, ids=[c[0] for c in FUSED_CASES])
+def test_reposition_score_in_one_call(name, spec, extra, fused):
+    """ifkv_reposition_score against the two calls it stands for (caches and scores bit for bit, also
+    when accumulating onto earlier scores) and against the oracle."""
+    wl = make_workload(spec)
+    k, v, q = oracle_inputs(wl)
+    n_ctx = wl.n_ctx
+    kw = {}
+    if "layout" in extra:
+        lay = layouts_for(spec, n_ctx)[extra["layout"]]
+        kw = dict(token_stride=lay[0], head_stride=lay[1])
+    L = make_layer(spec, max_ctx=n_ctx, max_prompt=spec.m_prompt, flags=extra.get("flags", 0), **kw)
+    L.set_tuning("fused_repo_score", 1 if fused else 0)
+    kd, vd = dev_chunks(wl)
+    if extra.get("no_v"):
+        vd = None
+    qd = to_dev(wl.q_prompt, spec.dtype)
+    order = wl.chunk_order.tolist()
+    rk = {key: extra[key] for key in ("cached_pos0", "delta_override") if key in extra}
+    kp_st = None
+    if extra.get("with_k_prompt"):
+        g = np.random.Generator(np.random.Philox(key=[spec.seed, 31]))
+        kp_st = to_storage(g.standard_normal((spec.m_prompt, spec.n_kv_heads, spec.head_dim)) * spec.sigma, spec.dtype)
+    kpd = None if kp_st is None else to_dev(kp_st, spec.dtype)
+    # the two calls
+    K1, V1, starts1, N1 = L.reposition_keys(kd, vd, chunk_order=order, **rk)
+    s1 = L.score_tokens(K1, qd, k_prompt=kpd)
+    # the one call, into caches that hold something else
+    K2, V2 = L.empty_cache(n_ctx), (None if vd is None else L.empty_cache(n_ctx))
+    K2.fill_(7.0)
+    K2, V2, starts2, N2, s2 = L.reposition_score(kd, vd, qd, chunk_order=order, k_out=K2, v_out=V2, k_prompt=kpd, **rk)
+    sync()
+    assert starts1 == starts2 and N1 == N2 == n_ctx
+    assert np.array_equal(to_host_bits(K1, spec.dtype), to_host_bits(K2, spec.dtype))
+    if vd is not None:
+        assert np.array_equal(to_host_bits(V1, spec.dtype), to_host_bits(V2, spec.dtype))
+    assert torch.equal(s1, s2)
+    # accumulate: a second layer's scores on top
+    s3 = s2.clone()
+    L.reposition_score(kd, vd, qd, chunk_order=order, k_out=K2, v_out=V2, k_prompt=kpd, scores=s3, accumulate=True, **rk)
+    s4 = s1.clone()
+    L.score_tokens(K1, qd, k_prompt=kpd, scores=s4, accumulate=True)
+    sync()
+    assert torch.equal(s3, s4)
+    # the oracle
+    K_ref, _, start_ref, _ = O.reposition_keys(k, v, wl.chunk_len, order, spec.rope_theta, spec.pairing,
+                                               cached_pos0=rk.get("cached_pos0"), delta_override=rk.get("delta_override"))
+    assert starts2 == start_ref.tolist()
+    check_reposition(to_host_f64(K2, spec.dtype), K_ref, spec.dtype, spec.pairing)
+    s_ref = O.score_tokens(to_host_f64(K2, spec.dtype), q, wl.sm_scale,
+                           k_prompt=None if kp_st is None else to_f64(kp_st, spec.dtype))
+    rtol = 1e-5 if spec.dtype == "f32" else 1e-2
+    assert (np.abs(s2.cpu().numpy() - s_ref) <= score_tol(s_ref, spec.m_prompt, rtol)).all()
+    L.close()
+
+
+# ---------------------------------------------------------------------------
 # stage 3
 # ---------------------------------------------------------------------------
 def topk_case(n, kind, seed):
