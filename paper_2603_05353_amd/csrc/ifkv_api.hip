@@ -51,6 +51,19 @@ int ensure_scratch(ifkv_ctx *ctx) {
     (void)hipGetLastError();
     return fail(ctx, IFKV_ENOMEM, "scratch allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
   }
+  // stage 2's arrival counters live apart from the shared scratch (other stages would overwrite them)
+  // and must read zero before the first launch; every launch leaves them at zero again
+  void *c = nullptr;
+  const size_t cbytes = ifkv::kScoreMaxKeyRanges * sizeof(int);
+  e = hipMalloc(&c, cbytes);
+  if (e == hipSuccess) e = hipMemset(c, 0, cbytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    if (c != nullptr) (void)hipFree(c);
+    (void)hipFree(p);
+    return fail(ctx, IFKV_ENOMEM, "counter allocation failed: %s", hipGetErrorString(e));
+  }
+  ctx->score_arrived = static_cast<int *>(c);
   ctx->scratch = p;
   ctx->scratch_bytes = bytes;
   return IFKV_OK;
@@ -149,6 +162,7 @@ int ifkv_create(ifkv_ctx **out, const ifkv_layer_desc *desc, void *hip_stream) {
 void ifkv_destroy(ifkv_ctx *ctx) {
   if (ctx == nullptr) return;
   if (ctx->scratch != nullptr) (void)hipFree(ctx->scratch);
+  if (ctx->score_arrived != nullptr) (void)hipFree(ctx->score_arrived);
   if (ctx->d_inv_freq != nullptr) (void)hipFree(ctx->d_inv_freq);
   delete ctx;
 }

@@ -29,6 +29,7 @@ struct ifkv_ctx {
   double *d_inv_freq = nullptr; // device copy, uploaded on first use
   void *scratch = nullptr;      // device scratch shared by the stages, allocated once
   size_t scratch_bytes = 0;
+  int *score_arrived = nullptr; // stage 2: blocks of a key range that have finished; zero between launches
   std::string err;
 };
 

@@ -263,9 +263,11 @@ hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, cons
     float2 *partial = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.partial_off);
     float2 *stats = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.stats_off);
     const int rows = d.n_q_heads * m_prompt;
-    hipLaunchKernelGGL((score_merge_kernel<BF16Tag, 128>), dim3((rows + 63) / 64), dim3(64), 0, ctx->stream, partial,
-                       n_slices, q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
-    return launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, true, accumulate, scores);
+    if (k_prompt != nullptr)  // the normaliser also runs over the prompt keys: the merge kernel folds them in
+      hipLaunchKernelGGL((score_merge_kernel<BF16Tag, 128>), dim3((rows + 63) / 64), dim3(64), 0, ctx->stream, partial,
+                         n_slices, q_prompt, k_prompt, m_prompt, d.n_q_heads, d.n_kv_heads, ctx->sm_scale, stats);
+    return launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, true, accumulate, scores, nullptr,
+                                    k_prompt != nullptr);
   }
   if (d.dtype == IFKV_BF16) {
     if (d.head_dim == 128) return run_generic<BF16Tag, 128>(ctx, k_global, n_ctx, q_prompt, m_prompt, k_prompt, accumulate, scores);

@@ -36,10 +36,13 @@ ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prom
 
 bool score_mfma_supported(const ifkv_ctx *ctx, int m_prompt);
 // pass_b == false: per-block partial (max, sum) of every (head, prompt row); *n_slices_out = number of
-// partials per row.  pass_b == true: column sums with the merged statistics, reduced into `scores`.
+// partials per row.  pass_b == true: column sums, reduced into `scores`; merged_stats says whether the
+// merge kernel has run (it must when the prompt keys take part) or pass B merges the partials itself.
 // `fused` (pass A only): the keys come from the chunk caches, see FusedRepo.
 hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
                                     int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores,
-                                    const FusedRepo *fused = nullptr);
+                                    const FusedRepo *fused = nullptr, bool merged_stats = false);
+// Key ranges (blocks along the context) of the MFMA sweeps: at most one per compute unit.
+constexpr int kScoreMaxKeyRanges = 256;
 
 }  // namespace ifkv

@@ -460,11 +460,39 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
 // ---------------------------------------------------------------------------
 // pass B
 // ---------------------------------------------------------------------------
+// What pass B needs besides the keys and queries.  Either `stats` (final (max, 1/Z) per (head, prompt
+// row), written by the merge kernel, which also folds in the prompt keys) or, when it is null, the
+// per-slice partials of pass A, which every block merges for its own query rows while its first
+// operands are on their way: one launch less.  The per-(kv head, query chunk) column sums go to
+// `colpart`; the block that is the last of a key range to finish (counted in `arrived`, which reads
+// zero between launches) adds them up in a fixed order and writes the scores: another launch less.
+struct ColsumIo {
+  const float2 *stats;
+  const float2 *partial;
+  int n_slices;
+  float *colpart;
+  int *arrived;     // [key ranges]
+  float *scores;
+  float inv_heads;
+  int accumulate;
+};
+
+// The column sums travel between blocks that sit on different XCDs, whose L2s are not coherent with
+// each other: they are written and read with device-scope relaxed atomics (write-through stores,
+// loads that do not hit a stale line) instead of cache-wide write-backs and invalidations.
+__device__ __forceinline__ void store_coherent(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_coherent(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, kWpe))) void score_colsum_mfma(
-    const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm,
-    const float2 *__restrict__ stats, float *__restrict__ colpart) {
+    const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm, ColsumIo io) {
   __shared__ __attribute__((aligned(16))) uint16_t q_lds[kQChunk * QSTR];
   __shared__ __attribute__((aligned(16))) float b_lds[kQChunk];
+  __shared__ int s_last;
+  float *const colpart = io.colpart;
   const int G = gm.n_q_heads / gm.n_kv_heads;
   const int kb = blockIdx.x;
   const int g = blockIdx.y / gm.n_qchunks;
@@ -498,7 +526,34 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
     int h, r;
     float b = INFINITY;  // padded rows contribute exp2(-inf) = 0
     if (q_row_address(gm, g, qc, ql, &off, &h, &r)) {
-      const float2 st = stats[h * gm.m_prompt + r];  // (max, 1/Z), natural-log domain
+      float2 st;  // (max, 1/Z), natural-log domain
+      if (io.stats != nullptr) {
+        st = io.stats[h * gm.m_prompt + r];
+      } else {
+        // the arithmetic of the merge kernel, slice partials eight at a time (independent loads)
+        float m = -INFINITY, z = 0.f;
+        for (int s0 = 0; s0 < io.n_slices; s0 += 8) {
+          float2 p[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            p[u] = make_float2(-INFINITY, 0.f);
+            if (s0 + u < io.n_slices) p[u] = io.partial[(static_cast<int64_t>(s0 + u) * gm.n_q_heads + h) * gm.m_prompt + r];
+          }
+          float mn = m;
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (p[u].y > 0.f) mn = fmaxf(mn, p[u].x);
+          if (mn > -INFINITY) {
+            float acc = z * expf(m - mn);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              if (p[u].y > 0.f) acc += p[u].y * expf(p[u].x - mn);
+            z = acc;
+            m = mn;
+          }
+        }
+        st = make_float2(m, z > 0.f ? 1.f / z : 0.f);
+      }
       b = st.y > 0.f ? st.x * kLog2e - __log2f(st.y) : INFINITY;
     }
     b_lds[ql] = b;
@@ -571,21 +626,30 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
       col0 += __shfl_xor(col0, 32, 64);
     col1 += __shfl_xor(col1, 32, 64);
     if (hf == 0) {
-      if (j0 + row < kv_end) dst[j0 + row] = col0;
-      if (j0 + 32 + row < kv_end) dst[j0 + 32 + row] = col1;
+      if (j0 + row < kv_end) store_coherent(&dst[j0 + row], col0);
+      if (j0 + 32 + row < kv_end) store_coherent(&dst[j0 + 32 + row], col1);
     }
   }
-}
-
-// scores[j] = (accumulate ? scores[j] : 0) + (1 / H_q) * sum over (kv head, chunk) partials
-__global__ void score_reduce_kernel(const float *__restrict__ colpart, int n_parts, int n_ctx, float inv_heads,
-                                    int accumulate, float *__restrict__ scores) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n_ctx) return;
-  float s = 0.f;
-  for (int p = 0; p < n_parts; ++p) s += colpart[static_cast<int64_t>(p) * n_ctx + j];
-  s *= inv_heads;
-  scores[j] = accumulate ? scores[j] + s : s;
+  // This block's column sums have reached memory when its stores have completed; the block that
+  // completes the count of its key range adds up all partials of the range.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int n_parts = static_cast<int>(gridDim.y);
+    const int done = __hip_atomic_fetch_add(&io.arrived[kb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+    s_last = done == n_parts ? 1 : 0;
+    if (done == n_parts) __hip_atomic_store(&io.arrived[kb], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (s_last != 0) {
+    const int n_parts = static_cast<int>(gridDim.y);
+    for (int j = kv_begin + threadIdx.x; j < kv_end; j += kThreads) {
+      float sum = 0.f;
+      for (int p = 0; p < n_parts; ++p) sum += load_coherent(&colpart[static_cast<int64_t>(p) * gm.n_ctx + j]);
+      sum *= io.inv_heads;
+      io.scores[j] = io.accumulate ? io.scores[j] + sum : sum;
+    }
+  }
 }
 
 }  // namespace
@@ -604,7 +668,7 @@ bool fused_repo_score_supported(const ifkv_ctx *ctx, int m_prompt, int n_chunks)
 
 hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
                                     int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores,
-                                    const FusedRepo *fused) {
+                                    const FusedRepo *fused, bool merged_stats) {
   static_assert(kMaxFusedChunks == kFusedMaxChunks, "one limit");
   static_assert(sizeof(FusedChunk) <= 32, "descriptor slot");
   const auto &d = ctx->desc;
@@ -688,12 +752,18 @@ hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t
     }
 #undef IFKV_LAUNCH_STATS
   } else {
+    if (ctx->score_arrived == nullptr || kv_blocks > kScoreMaxKeyRanges) return hipErrorInvalidValue;
+    ColsumIo io;
+    io.stats = merged_stats ? stats : nullptr;
+    io.partial = partial;
+    io.n_slices = kv_blocks;
+    io.colpart = colpart;
+    io.arrived = ctx->score_arrived;
+    io.scores = scores;
+    io.inv_heads = 1.0f / d.n_q_heads;
+    io.accumulate = accumulate;
     hipLaunchKernelGGL(score_colsum_mfma, grid, dim3(kThreads), 0, ctx->stream,
-                       static_cast<const uint16_t *>(k_global), static_cast<const uint16_t *>(q_prompt), gm, stats,
-                       colpart);
-    hipLaunchKernelGGL(score_reduce_kernel, dim3(static_cast<unsigned>((n_ctx + 255) / 256)), dim3(256), 0,
-                       ctx->stream, colpart, per_head, static_cast<int>(n_ctx), 1.0f / d.n_q_heads, accumulate,
-                       scores);
+                       static_cast<const uint16_t *>(k_global), static_cast<const uint16_t *>(q_prompt), gm, io);
   }
   return hipGetLastError();
 }
