@@ -25,10 +25,11 @@
  *   call is made; "host" pointers are ordinary host memory, read before the
  *   call returns.  The caller owns every buffer passed in; the library never
  *   frees, reallocates or keeps a caller pointer after the call's kernels end.
- *   The context owns only its own scratch memory: one allocation, sized from
- *   the layer descriptor (max_ctx, max_prompt, head counts), made by the first
- *   stage call that needs scratch and freed by ifkv_destroy.  No later call
- *   allocates, frees or synchronises.
+ *   The context owns only its own scratch memory: one allocation (and a 1 KiB
+ *   block of counters beside it), sized from the layer descriptor (max_ctx,
+ *   max_prompt, head counts), made by the first stage call that needs scratch
+ *   and freed by ifkv_destroy.  No later call allocates, frees or synchronises
+ *   (except under IFKV_FLAG_VALIDATE, which synchronises by design).
  * - All device work is enqueued on the context's HIP stream and the calls
  *   return without waiting for it.  Host outputs (chunk starts, N, k) are
  *   computed on the host from host inputs and are valid on return.

@@ -12,8 +12,15 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kBatch = 4;      // independent 16-byte loads in flight per thread and stream
-constexpr int kRepoRows = 8;   // stage 1: rows per tile (16 KiB of keys and of values at 8 x 128 bf16)
-constexpr int kRepoBatch = 4;  // stage 1: work items per thread and batch, four 16-byte loads each
+// Stage 1 tile shape; the two macros exist so that a build can sweep them (-DIFKV_REPO_ROWS=..).
+#ifndef IFKV_REPO_ROWS
+#define IFKV_REPO_ROWS 8
+#endif
+#ifndef IFKV_REPO_BATCH
+#define IFKV_REPO_BATCH 4
+#endif
+constexpr int kRepoRows = IFKV_REPO_ROWS;    // stage 1: rows per tile (16 KiB of keys and of values at 8 x 128 bf16)
+constexpr int kRepoBatch = IFKV_REPO_BATCH;  // stage 1: work items per thread and batch, four 16-byte loads each
 
 // ---------------------------------------------------------------------------
 // Stage 1.  Method, Eq. (5): global position = chunk start + local index; a
