@@ -10,6 +10,8 @@
 //
 // This file holds the plain fp32 ALU kernels (any dtype; used for fp32 layers
 // and for cross-checking).  The bf16 MFMA kernels live in score_mfma.hip.
+#include <algorithm>
+
 #include "ifkv_device.h"
 #include "ifkv_internal.h"
 #include "score_common.h"
@@ -230,7 +232,11 @@ ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prom
   const int64_t max_slices = 256;  // upper bound for both the ALU and the MFMA partition
   s.stats_off = 0;
   s.partial_off = ((rows * sizeof(float2) + 255) / 256) * 256;
-  s.fused_off = s.partial_off + ((max_slices * rows * sizeof(float2) + 255) / 256) * 256;
+  // the MFMA sweeps without a merge kernel keep them per block: at most max(256, kv heads x query
+  // chunks) blocks of at most 512 rows
+  const int64_t mfma_blocks = std::max<int64_t>(256, static_cast<int64_t>(d.n_kv_heads) * kMaxQChunks);
+  const int64_t partial_entries = std::max<int64_t>(max_slices * rows, mfma_blocks * 512);
+  s.fused_off = s.partial_off + ((partial_entries * sizeof(float2) + 255) / 256) * 256;
   s.colpart_off = s.fused_off + ((kFusedTableBytes + 255) / 256) * 256;
   // per-(kv head, query chunk) partial column sums of the MFMA pass B
   const int64_t parts = static_cast<int64_t>(d.n_kv_heads) * kMaxQChunks;
@@ -257,7 +263,8 @@ hipError_t launch_score(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, cons
   if (!generic) {
     // MFMA sweeps around the same merge kernel (which also folds in the prompt keys)
     int n_slices = 0;
-    hipError_t e = launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, false, 0, nullptr, fused);
+    hipError_t e = launch_score_mfma_passes(ctx, k_global, n_ctx, q_prompt, m_prompt, &n_slices, false, 0, nullptr, fused,
+                                            k_prompt != nullptr);
     if (e != hipSuccess) return e;
     ScoreScratch sc = score_scratch_layout(ctx, n_ctx, m_prompt);
     float2 *partial = reinterpret_cast<float2 *>(static_cast<char *>(ctx->scratch) + sc.partial_off);

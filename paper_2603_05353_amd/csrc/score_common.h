@@ -36,8 +36,9 @@ ScoreScratch score_scratch_layout(const ifkv_ctx *ctx, int64_t n_ctx, int m_prom
 
 bool score_mfma_supported(const ifkv_ctx *ctx, int m_prompt);
 // pass_b == false: per-block partial (max, sum) of every (head, prompt row); *n_slices_out = number of
-// partials per row.  pass_b == true: column sums, reduced into `scores`; merged_stats says whether the
-// merge kernel has run (it must when the prompt keys take part) or pass B merges the partials itself.
+// partials per row.  pass_b == true: column sums, reduced into `scores`.  merged_stats (the same value in
+// both calls of a pair) says whether the merge kernel runs between them (it must when the prompt keys take
+// part) or pass B merges the partials itself; the layout of the partials follows from it.
 // `fused` (pass A only): the keys come from the chunk caches, see FusedRepo.
 hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
                                     int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores,

@@ -46,6 +46,10 @@ struct ScoreGeom {
   int n_qchunks;   // query-row chunks per kv head
   int q_chunk_rows;  // rows per chunk (multiple of 128, <= kQChunk); the last chunk may hold fewer
   int kv_per_block;
+  // Layout of the per-slice partials.  0: [slice][query head][prompt row], what the merge kernel
+  // reads.  1: [slice][kv head, query chunk][row of the chunk], the order in which a block of the
+  // second sweep holds its rows, so that its own merge reads whole lines.
+  int partial_by_block;
   float scale_log2;
   int64_t token_stride, head_stride;  // layout of k_global, in elements
 };
@@ -317,7 +321,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
     for (int i = threadIdx.x; i < fa.n_chunks; i += kThreads) s_starts[i] = fa.starts[i];
     __syncthreads();
   }
-  auto next_keys = [&](bf16x8 (&dst)[2][8], int j) {
+  auto next_keys = [&](bf16x8 (&dst)[2][8], int j) __attribute__((always_inline)) {
     if (FUSED)
       fused_k_frags(dst, fa, s_starts, gm, g, j, row, hf, qc == 0);
     else
@@ -357,13 +361,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
   //
   // Software pipeline over the query blocks.  pipe_step issues the sixteen MFMAs of block qn into
   // (N0, N1) in eight slices of two; each slice is followed by a share of the vector work on the
-  // finished block (C0, C1): slice 0 takes the running maximum, slices 1..7 the exponentials and
-  // the sum.  The fences keep the slices in this order, so the matrix pipe works underneath the
-  // vector instructions of the same wavefront.  The last step of a tile issues one block whose
-  // products are not used.  tail_tag (a compile-time tag, for the same reason as NQB) selects the
-  // variant for a ragged last tile, which masks the keys past the end.
-  auto pipe_step = [&](auto tail_tag, f32x16 &N0, f32x16 &N1, int qn, f32x16 &C0, f32x16 &C1, float &mq, float &zq,
-                       int j0) {
+  // finished block (C0, C1).  The fences keep the slices in this order, so the matrix pipe works
+  // underneath the vector instructions of the same wavefront.  The last step of a tile issues one
+  // block whose products are not used.  tail_tag (a compile-time tag, for the same reason as NQB)
+  // selects the variant for a ragged last tile, which masks the keys past the end.
+  //
+  // Two variants of the vector work (exact_tag).  The sums only need SOME reference exponent per row
+  // that keeps them inside the fp32 range, not the row maximum: the fast variant takes the logit of
+  // the first key a lane sees for the row (always the logit of a real key, because the key loads
+  // are clamped to the last key of the context) and keeps it for the whole sweep, which saves the
+  // maximum over every tile and the rescaling: slice s handles four of the 32 values.  Sums that
+  // leave [0, 2^60] (a logit more than 60 above the reference: attention far more peaked than
+  // anything a model produces) make the block repeat its sweep with the exact variant, which keeps
+  // a running maximum: slice 0 takes the maximum, slices 1..7 the exponentials and the sum.
+  auto pipe_step = [&](auto tail_tag, auto exact_tag, f32x16 &N0, f32x16 &N1, int qn, f32x16 &C0, f32x16 &C1,
+                       float &mq, float &zq, int j0, bool first) __attribute__((always_inline)) {
+    constexpr bool kExact = decltype(exact_tag)::value;
+    const float first_logit = C0[0];  // taken before the mask
     if (decltype(tail_tag)::value) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -378,23 +392,35 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
     for (int s = 0; s < 8; ++s) {
       bf16x8 qf_next = qf;
       if (s < 7) qf_next = q_frag_a(qn, s + 1);
-      qk_step<true>(N0, N1, kf, qf, s);
       // The empty asm statements tie the vector work to its slice: they are ordered against the
       // fences, the values that pass through them cannot be formed earlier or used later, so the
       // instruction selector cannot collect the vector work of all slices behind the last MFMA.
-      if (s == 0) {
-        float mx = C0[0];
+      if (kExact) {
+        qk_step<true>(N0, N1, kf, qf, s);
+        if (s == 0) {
+          float mx = C0[0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(fmaxf(mx, C0[r]), C1[r]);  // chain form: one v_max3 per pair
-        m_new = fmaxf(mq, mx * c);
-        m_use = fmaxf(m_new, -1e30f);  // a lane that has seen no valid key yet stays at (-inf, 0)
-        asm volatile("" : "+v"(m_use));
+          for (int r = 0; r < 16; ++r) mx = fmaxf(fmaxf(mx, C0[r]), C1[r]);  // chain form: one v_max3 per pair
+          m_new = fmaxf(mq, mx * c);
+          m_use = fmaxf(m_new, -1e30f);  // a lane that has seen no valid key yet stays at (-inf, 0)
+          asm volatile("" : "+v"(m_use));
+        } else {
+          // 32 values over seven slices: registers [lo, hi) of both halves
+          const int lo = ((s - 1) * 16) / 7, hi = (s * 16) / 7;
+          asm volatile("" : "+v"(m_use));
+#pragma unroll
+          for (int r = lo; r < hi; ++r) {
+            acc += __builtin_amdgcn_exp2f(fmaf(C0[r], c, -m_use));
+            acc += __builtin_amdgcn_exp2f(fmaf(C1[r], c, -m_use));
+          }
+          asm volatile("" : "+v"(acc));
+        }
       } else {
-        // 32 values over seven slices: registers [lo, hi) of both halves
-        const int lo = ((s - 1) * 16) / 7, hi = (s * 16) / 7;
+        qk_step<true>(N0, N1, kf, qf, s);
+        if (s == 0) m_use = first ? first_logit * c : mq;
         asm volatile("" : "+v"(m_use));
 #pragma unroll
-        for (int r = lo; r < hi; ++r) {
+        for (int r = 2 * s; r < 2 * s + 2; ++r) {
           acc += __builtin_amdgcn_exp2f(fmaf(C0[r], c, -m_use));
           acc += __builtin_amdgcn_exp2f(fmaf(C1[r], c, -m_use));
         }
@@ -403,27 +429,55 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
       __builtin_amdgcn_sched_barrier(0);
       qf = qf_next;
     }
-    zq = zq * __builtin_amdgcn_exp2f(mq - m_use) + acc;
-    mq = m_new;
+    if (kExact) {
+      zq = zq * __builtin_amdgcn_exp2f(mq - m_use) + acc;
+      mq = m_new;
+    } else {
+      zq += acc;
+      mq = m_use;
+    }
   };
-  auto tile = [&](auto tail_tag, int j0) {
+  auto tile = [&](auto tail_tag, auto exact_tag, int j0, bool first) __attribute__((always_inline)) {
     f32x16 A0, A1, B0, B1;
 #pragma unroll
     for (int s = 0; s < 8; ++s) qk_step<true>(A0, A1, kf, q_frag_a(0, s), s);  // block 0, nothing interleaved
 #pragma unroll
     for (int qb = 0; qb < NQB; qb += 2) {
-      pipe_step(tail_tag, B0, B1, qb + 1, A0, A1, m[qb], z[qb], j0);
-      pipe_step(tail_tag, A0, A1, qb + 2 < NQB ? qb + 2 : NQB - 1, B0, B1, m[qb + 1], z[qb + 1], j0);
+      pipe_step(tail_tag, exact_tag, B0, B1, qb + 1, A0, A1, m[qb], z[qb], j0, first);
+      pipe_step(tail_tag, exact_tag, A0, A1, qb + 2 < NQB ? qb + 2 : NQB - 1, B0, B1, m[qb + 1], z[qb + 1], j0, first);
     }
   };
-  for (; j0 < kv_end; j0 += kWaves * kTile) {
-    if (j0 + kTile > kv_end)
-      tile(std::true_type{}, j0);
-    else
-      tile(std::false_type{}, j0);
-    const int j_next = j0 + kWaves * kTile;
-    if (j_next < kv_end) next_keys(kf, j_next);
+  const int j_first = j0;
+  auto sweep = [&](auto exact_tag) __attribute__((always_inline)) {
+    for (; j0 < kv_end; j0 += kWaves * kTile) {
+      if (j0 + kTile > kv_end)
+        tile(std::true_type{}, exact_tag, j0, j0 == j_first);
+      else
+        tile(std::false_type{}, exact_tag, j0, j0 == j_first);
+      const int j_next = j0 + kWaves * kTile;
+      if (j_next < kv_end) next_keys(kf, j_next);
+    }
+  };
+  sweep(std::false_type{});
+  {
+    bool out_of_range = false;
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) out_of_range |= !(z[qb] <= 0x1p60f);  // also true for NaN
+    if (__syncthreads_or(out_of_range ? 1 : 0)) {  // uniform over the block
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        m[qb] = -INFINITY;
+        z[qb] = 0.f;
+      }
+      j0 = j_first;
+      if (j0 < kv_end) next_keys(kf, j0);
+      sweep(std::true_type{});
+    }
   }
+  // a lane half that saw no valid key, or whose terms all vanished against its reference, takes no part
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb)
+    if (!(z[qb] > 0.f)) m[qb] = -INFINITY;
 
   // merge the two lane halves (same query row, disjoint keys), then the wavefronts
   __syncthreads();
@@ -453,7 +507,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
     int h, r;
     q_row_address(gm, g, qc, ql, &off, &h, &r);
     // natural-log domain, as the merge kernel expects
-    partial[(static_cast<int64_t>(kb) * gm.n_q_heads + h) * gm.m_prompt + r] = make_float2(mm * kLn2, zz);
+    const int64_t at = gm.partial_by_block
+                           ? (static_cast<int64_t>(kb) * gridDim.y + blockIdx.y) * gm.q_chunk_rows + ql
+                           : (static_cast<int64_t>(kb) * gm.n_q_heads + h) * gm.m_prompt + r;
+    partial[at] = make_float2(mm * kLn2, zz);
   }
 }
 
@@ -487,6 +544,33 @@ __device__ __forceinline__ float load_coherent(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Slices s0 .. s0 + kMergeBatch - 1 of one query row's partials (independent loads; a slice past the
+// last one reads the last one again and is ignored by merge_partials).
+constexpr int kMergeBatch = 32;
+__device__ __forceinline__ void load_partials(float2 (&p)[kMergeBatch], const float2 *row, int slice_stride, int s0,
+                                              int n_slices) {
+#pragma unroll
+  for (int u = 0; u < kMergeBatch; ++u) p[u] = row[min(s0 + u, n_slices - 1) * slice_stride];
+}
+// What the merge kernel computes, kMergeBatch slices at a time, with the hardware exponential (one
+// instruction instead of a library call: 32 of those per row held every block up for 3 us).
+__device__ __forceinline__ void merge_partials(const float2 (&p)[kMergeBatch], int s0, int n_slices, float &m, float &z) {
+  float mn = m;
+#pragma unroll
+  for (int u = 0; u < kMergeBatch; ++u)
+    if (s0 + u < n_slices && p[u].y > 0.f) mn = fmaxf(mn, p[u].x);
+  if (mn > -INFINITY) {
+    float acc = z * __builtin_amdgcn_exp2f((m - mn) * kLog2e);
+#pragma unroll
+    for (int u = 0; u < kMergeBatch; ++u) {
+      const float w = s0 + u < n_slices && p[u].y > 0.f ? p[u].y : 0.f;
+      acc += w * __builtin_amdgcn_exp2f(fminf(p[u].x - mn, 0.f) * kLog2e);
+    }
+    z = acc;
+    m = mn;
+  }
+}
+
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, kWpe))) void score_colsum_mfma(
     const uint16_t *__restrict__ k_global, const uint16_t *__restrict__ q_prompt, ScoreGeom gm, ColsumIo io) {
   __shared__ __attribute__((aligned(16))) uint16_t q_lds[kQChunk * QSTR];
@@ -508,55 +592,56 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
   // the query tile and the first key tile are requested together, before anything waits
   bf16x8 kf[2][8];
   int j0 = kv_begin + wave * kTile;
-  auto stage_q = [&](auto nv_tag) {
+  // This thread's query row (a chunk holds at most kThreads rows).  When the block merges the
+  // per-slice partials itself, the first kMergeBatch of them are requested first (they come from
+  // memory: other blocks wrote them in the previous launch), then the query tile and the first key
+  // tile, and the merge arithmetic runs while the key tile is on its way.
+  static_assert(kQChunk <= kThreads, "one query row per thread");
+  const int ql = threadIdx.x;
+  const bool merge_here = io.stats == nullptr;
+  auto my_partials = [&]() __attribute__((always_inline)) {
+    return io.partial + blockIdx.y * gm.q_chunk_rows + min(ql, gm.q_chunk_rows - 1);
+  };
+  const int slice_stride = static_cast<int>(gridDim.y) * gm.q_chunk_rows;  // at most 256 blocks of 512 rows
+  auto softmax_offsets = [&](const float2 (&part)[kMergeBatch]) __attribute__((always_inline)) {
+    if (ql < nqb * 32) {
+      int64_t off;
+      int h, r;
+      float b = INFINITY;  // padded rows contribute exp2(-inf) = 0
+      if (q_row_address(gm, g, qc, ql, &off, &h, &r)) {
+        float2 st;  // (max, 1/Z), natural-log domain
+        if (!merge_here) {
+          st = io.stats[h * gm.m_prompt + r];
+        } else {
+          float m = -INFINITY, z = 0.f;
+          merge_partials(part, 0, io.n_slices, m, z);
+          for (int s0 = kMergeBatch; s0 < io.n_slices; s0 += kMergeBatch) {
+            float2 more[kMergeBatch];
+            load_partials(more, my_partials(), slice_stride, s0, io.n_slices);
+            merge_partials(more, s0, io.n_slices, m, z);
+          }
+          st = make_float2(m, z > 0.f ? 1.f / z : 0.f);
+        }
+        b = st.y > 0.f ? st.x * kLog2e - __log2f(st.y) : INFINITY;
+      }
+      b_lds[ql] = b;
+    }
+  };
+  auto stage_q = [&](auto nv_tag) __attribute__((always_inline)) {
     constexpr int NV = decltype(nv_tag)::value;
+    float2 part[kMergeBatch];
+    if (merge_here) load_partials(part, my_partials(), slice_stride, 0, io.n_slices);
     v4u qx[NV];
     q_tile_request<NV>(qx, q_prompt, gm, g, qc);
     if (j0 < kv_end) load_k_frags(kf, k_global, gm, g, j0, row, hf);
-    q_tile_store<NV>(q_lds, qx);
+    q_tile_store<NV>(q_lds, qx);  // the query tile arrives before the key tile
+    softmax_offsets(part);
   };
   switch (gm.q_chunk_rows >> 7) {  // uniform over the grid
     case 1: stage_q(std::integral_constant<int, 4>{}); break;
     case 2: stage_q(std::integral_constant<int, 8>{}); break;
     case 3: stage_q(std::integral_constant<int, 12>{}); break;
     default: stage_q(std::integral_constant<int, 16>{}); break;
-  }
-  for (int ql = threadIdx.x; ql < nqb * 32; ql += kThreads) {
-    int64_t off;
-    int h, r;
-    float b = INFINITY;  // padded rows contribute exp2(-inf) = 0
-    if (q_row_address(gm, g, qc, ql, &off, &h, &r)) {
-      float2 st;  // (max, 1/Z), natural-log domain
-      if (io.stats != nullptr) {
-        st = io.stats[h * gm.m_prompt + r];
-      } else {
-        // the arithmetic of the merge kernel, slice partials eight at a time (independent loads)
-        float m = -INFINITY, z = 0.f;
-        for (int s0 = 0; s0 < io.n_slices; s0 += 8) {
-          float2 p[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            p[u] = make_float2(-INFINITY, 0.f);
-            if (s0 + u < io.n_slices) p[u] = io.partial[(static_cast<int64_t>(s0 + u) * gm.n_q_heads + h) * gm.m_prompt + r];
-          }
-          float mn = m;
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-            if (p[u].y > 0.f) mn = fmaxf(mn, p[u].x);
-          if (mn > -INFINITY) {
-            float acc = z * expf(m - mn);
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-              if (p[u].y > 0.f) acc += p[u].y * expf(p[u].x - mn);
-            z = acc;
-            m = mn;
-          }
-        }
-        st = make_float2(m, z > 0.f ? 1.f / z : 0.f);
-      }
-      b = st.y > 0.f ? st.x * kLog2e - __log2f(st.y) : INFINITY;
-    }
-    b_lds[ql] = b;
   }
   __syncthreads();
 
@@ -574,7 +659,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
   // block qn, which the next call consumes as bc.
   auto pipe_step = [&](const bf16x8 (&kf)[2][8], bf16x8 (&qf)[4], f32x16 &N0, f32x16 &N1, int qn, int qn2,
                        const f32x16 &C0, const f32x16 &C1, const f32x4 (&bc)[4], f32x4 (&bn)[4], float &col0,
-                       float &col1) {
+                       float &col1) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       qf[(s + 3) & 3] = s + 3 < 8 ? q_frag(q_lds, qn, s + 3, row, hf) : q_frag(q_lds, qn2, s + 3 - 8, row, hf);
@@ -623,7 +708,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWpe, 
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) kf[t][s2] = kf_next[t][s2];
     }
-      col0 += __shfl_xor(col0, 32, 64);
+    col0 += __shfl_xor(col0, 32, 64);
     col1 += __shfl_xor(col1, 32, 64);
     if (hf == 0) {
       if (j0 + row < kv_end) store_coherent(&dst[j0 + row], col0);
@@ -669,6 +754,7 @@ bool fused_repo_score_supported(const ifkv_ctx *ctx, int m_prompt, int n_chunks)
 hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t n_ctx, const void *q_prompt,
                                     int m_prompt, int *n_slices_out, bool pass_b, int accumulate, float *scores,
                                     const FusedRepo *fused, bool merged_stats) {
+  // merged_stats: the merge kernel runs between the sweeps (both calls of a pair pass the same value)
   static_assert(kMaxFusedChunks == kFusedMaxChunks, "one limit");
   static_assert(sizeof(FusedChunk) <= 32, "descriptor slot");
   const auto &d = ctx->desc;
@@ -685,6 +771,7 @@ hipError_t launch_score_mfma_passes(ifkv_ctx *ctx, const void *k_global, int64_t
   gm.n_qchunks = (m_prompt * G + kQChunk - 1) / kQChunk;
   gm.q_chunk_rows = ((m_prompt * G + gm.n_qchunks - 1) / gm.n_qchunks + 127) / 128 * 128;
   gm.scale_log2 = ctx->sm_scale * kLog2e;
+  gm.partial_by_block = merged_stats ? 0 : 1;
   // one block per CU when the context is long enough; a block owns whole 64-key tiles
   const int per_head = d.n_kv_heads * gm.n_qchunks;
   int kv_blocks = 256 / per_head;

@@ -238,6 +238,38 @@ def test_score_peaky_logits():
     L.close()
 
 
+@pytest.mark.parametrize("gain", [30.0, 70.0, 200.0])
+def test_score_prompt_rows_aligned_with_single_keys(gain):
+    """Every prompt row points at one key with a logit of `gain` (natural units) while the first keys a
+    wavefront sees score near zero: the first sweep of the MFMA path keeps the logit of the first key as
+    its reference exponent, so at 70 and 200 its sums leave the range it accepts and the block must repeat
+    the sweep with a running maximum; at 30 it must not need to."""
+    spec = preset("C3", chunk_lens=[300, 211, 150, 600], m_prompt=24)
+    wl = make_workload(spec)
+    K_st, K64, _ = global_keys(wl)
+    N, hq, hkv, d = wl.n_ctx, spec.n_q_heads, spec.n_kv_heads, spec.head_dim
+    G = hq // hkv
+    g = np.random.Generator(np.random.Philox(key=[77, int(gain)]))
+    targets = np.concatenate([[0, 1, 63, 64, 65, N - 1, N - 64, 511, 512], g.integers(0, N, size=64)])
+    q = np.empty((spec.m_prompt, hq, d))
+    for r in range(spec.m_prompt):
+        for h in range(hq):
+            kj = K64[targets[(r * hq + h) % len(targets)], h // G]
+            q[r, h] = gain * np.sqrt(d) * kj / (kj @ kj)
+    q_st = to_storage(q, "bf16")
+    s_ref = O.score_tokens(K64, to_f64(q_st, "bf16"), wl.sm_scale)
+    assert s_ref[np.unique(targets)].sum() > 0.9 * spec.m_prompt   # the mass sits on the targets
+    L = make_layer(spec, max_ctx=N, max_prompt=spec.m_prompt)
+    s = L.score_tokens(to_dev(K_st, "bf16"), to_dev(q_st, "bf16"))
+    sync()
+    s = s.cpu().numpy().astype(np.float64)
+    assert np.isfinite(s).all()
+    assert (np.abs(s - s_ref) <= score_tol(s_ref, spec.m_prompt, 1e-2)).all(), \
+        f"max rel {np.max(np.abs(s - s_ref) / (np.abs(s_ref) + spec.m_prompt / N))}"
+    assert abs(s.sum() - spec.m_prompt) < 1e-3 * spec.m_prompt
+    L.close()
+
+
 # ---------------------------------------------------------------------------
 # stages 1 + 2 in one call (the first scoring sweep reads the chunk caches)
 # ---------------------------------------------------------------------------
