@@ -238,12 +238,14 @@ def test_score_peaky_logits():
     L.close()
 
 
-@pytest.mark.parametrize("gain", [30.0, 70.0, 200.0])
-def test_score_prompt_rows_aligned_with_single_keys(gain):
+@pytest.mark.parametrize("gain,fused", [(30.0, False), (70.0, False), (200.0, False), (70.0, True)],
+                         ids=["logit30", "logit70", "logit200", "logit70-fused-sweep"])
+def test_score_prompt_rows_aligned_with_single_keys(gain, fused):
     """Every prompt row points at one key with a logit of `gain` (natural units) while the first keys a
     wavefront sees score near zero: the first sweep of the MFMA path keeps the logit of the first key as
     its reference exponent, so at 70 and 200 its sums leave the range it accepts and the block must repeat
-    the sweep with a running maximum; at 30 it must not need to."""
+    the sweep with a running maximum; at 30 it must not need to.  `fused`: the same through the sweep
+    that reads the chunk caches (ifkv_reposition_score with the fused sweep switched on)."""
     spec = preset("C3", chunk_lens=[300, 211, 150, 600], m_prompt=24)
     wl = make_workload(spec)
     K_st, K64, _ = global_keys(wl)
@@ -260,7 +262,12 @@ def test_score_prompt_rows_aligned_with_single_keys(gain):
     s_ref = O.score_tokens(K64, to_f64(q_st, "bf16"), wl.sm_scale)
     assert s_ref[np.unique(targets)].sum() > 0.9 * spec.m_prompt   # the mass sits on the targets
     L = make_layer(spec, max_ctx=N, max_prompt=spec.m_prompt)
-    s = L.score_tokens(to_dev(K_st, "bf16"), to_dev(q_st, "bf16"))
+    if fused:
+        L.set_tuning("fused_repo_score", 1)
+        kd, vd = dev_chunks(wl)
+        s = L.reposition_score(kd, vd, to_dev(q_st, "bf16"), chunk_order=wl.chunk_order.tolist())[4]
+    else:
+        s = L.score_tokens(to_dev(K_st, "bf16"), to_dev(q_st, "bf16"))
     sync()
     s = s.cpu().numpy().astype(np.float64)
     assert np.isfinite(s).all()
