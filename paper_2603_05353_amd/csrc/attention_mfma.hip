@@ -571,7 +571,8 @@ namespace {
 
 constexpr int kSlots = 512;       // workgroups the chip holds at a time (256 CUs, two each)
 constexpr int kMinPartTiles = 32;
-constexpr int kMaxParts = 8;
+constexpr int kMaxParts = 8;      // parts of a launch that fills the slots (the scratch is sized for this)
+constexpr int kMaxPartsFew = 64;  // launches with a handful of row blocks: as many parts as slots stay free
 
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
@@ -595,8 +596,11 @@ size_t partial_bytes(const ifkv_ctx *ctx, int64_t n_rows, int parts) {
 // no more jobs than slots are cut: with more, every slot is busy for most of the launch anyway and
 // the partial writes plus the combine pass cost more than the shorter tail gains (684 jobs: 0.469 ->
 // 0.479 ms; 1232 jobs: 1.28 -> 1.37 ms; cutting only the longest row blocks of such a launch: 1.23
-// -> 1.26 .. 1.33 ms).  A part spans at least 32 tiles and there are at most 8 parts, unless the
-// tuning knobs say otherwise; a cut whose partial results would not fit the scratch is not made.
+// -> 1.26 .. 1.33 ms).  A part spans at least 32 tiles and there are at most 8 parts -- with so few
+// row blocks that 8 parts each would leave slots empty (a few dozen rows against a long context), up
+// to 64, as long as jobs x parts stays within the slots, which also keeps the partial results within
+// the scratch -- unless the tuning knobs say otherwise; a cut whose partial results would not fit
+// the scratch is not made.
 struct SplitChoice {
   int parts, part_tiles;
 };
@@ -620,7 +624,9 @@ SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
   }
   if (!forced) {
     if (part_tiles < kMinPartTiles) part_tiles = kMinPartTiles;
-    if (part_tiles * kMaxParts < n_kv_tiles) part_tiles = (n_kv_tiles + kMaxParts - 1) / kMaxParts;
+    int max_parts = kMaxParts;
+    if (jobs > 0 && jobs * kMaxParts < kSlots) max_parts = static_cast<int>(std::min<int64_t>(kMaxPartsFew, kSlots / jobs));
+    if (part_tiles * max_parts < n_kv_tiles) part_tiles = (n_kv_tiles + max_parts - 1) / max_parts;
   }
   if (part_tiles < 1) part_tiles = 1;
   if (part_tiles > n_kv_tiles) part_tiles = n_kv_tiles > 0 ? n_kv_tiles : 1;

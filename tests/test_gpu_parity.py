@@ -487,6 +487,16 @@ def test_attention_parity_bf16(name, spec, k, flags):
     attention_case(spec, rows, flags=flags, n_check=300 if name.startswith("many-rows") else None)
 
 
+def test_attention_few_rows_against_a_long_context():
+    """A few dozen rows against 20K keys: so few row blocks that the library cuts the kv axis into more
+    than its usual 8 parts (8 jobs, 313 tiles: 10 parts of 32 tiles), merged by the combine pass."""
+    spec = preset("C3", chunk_lens=[2500] * 8, m_prompt=8)
+    rows = np.unique(np.concatenate([sample_rows(20000, 28, 21), [0, 63, 64, 19999]]))
+    assert len(rows) <= 32   # one row block per kv head
+    attention_case(spec, rows)
+    attention_case(spec, rows, q_gain=6.0)
+
+
 # (chunk lengths, selected rows or a count to draw, H_q, H_kv): caches shorter than / equal to / one past a
 # key tile, a single row, every row, the largest and the smallest group size the MFMA path takes
 ATTN_SHAPES = [
