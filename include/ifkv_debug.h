@@ -42,6 +42,22 @@ extern "C" {
  */
 int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value);
 
+/*
+ * Reports how ifkv_recompute_attention would serve a call of n_rows rows against
+ * n_kv keys under the context's descriptor and tuning, without launching
+ * anything: plan[0] = launches (more than 65535 row blocks take several),
+ * plan[1] = the largest number of kv parts any launch is cut into (1 = not
+ * cut), plan[2] = the shortest part, in 64-row tiles, plan[3] = the most bytes
+ * of partial results any launch keeps in scratch, plan[4] = the bytes of the
+ * context's scratch (as allocated, or as the first stage call will allocate
+ * it).  The library never makes a cut with plan[3] > plan[4]; the host tests
+ * check that over sweeps of shapes and knobs.
+ *
+ * Host only, no GPU call.  plan: host, 5 entries.  Errors: IFKV_EINVAL for a
+ * NULL context or plan, n_rows < 0, n_kv < 1 or beyond max_ctx.
+ */
+int ifkv_attention_plan(ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv, int64_t *plan);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = (
     "ifkv_reposition_keys", "ifkv_score_tokens", "ifkv_reposition_score", "ifkv_select_topk", "ifkv_select_topk_noalloc",
     "ifkv_recompute_attention", "ifkv_splice_kv", "ifkv_rope_rows", "ifkv_chunk_counts", "ifkv_reorder_chunks",
     "ifkv_copy_bytes", "ifkv_mfma_probe", "ifkv_mfma_probe_sink_floats",   # include/ifkv_calibrate.h
-    "ifkv_set_tuning",                                                       # include/ifkv_debug.h
+    "ifkv_set_tuning", "ifkv_attention_plan",                                # include/ifkv_debug.h
 )
 
 
@@ -102,6 +102,8 @@ def load_library() -> C.CDLL:
     lib.ifkv_mfma_probe_sink_floats.restype = i64
     lib.ifkv_set_tuning.argtypes = [vp, C.c_char_p, i64]
     lib.ifkv_set_tuning.restype = C.c_int
+    lib.ifkv_attention_plan.argtypes = [vp, i64, i64, C.POINTER(C.c_int64)]
+    lib.ifkv_attention_plan.restype = C.c_int
     _lib = lib
     return lib
 
@@ -380,6 +382,12 @@ class Layer:
     def set_tuning(self, key: str, value: int) -> None:
         """Tuning / testing knob of include/ifkv_debug.h (host only)."""
         self._check(self._lib.ifkv_set_tuning(self._ctx, key.encode(), int(value)))
+
+    def attention_plan(self, n_rows: int, n_kv: int) -> dict:
+        """How recompute_attention would serve such a call (include/ifkv_debug.h; host only)."""
+        out = (C.c_int64 * 5)()
+        self._check(self._lib.ifkv_attention_plan(self._ctx, int(n_rows), int(n_kv), out))
+        return dict(zip(("launches", "parts", "part_tiles", "partial_bytes", "scratch_bytes"), (int(x) for x in out)))
 
     def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor) -> None:
         self._check(self._lib.ifkv_copy_bytes(self._ctx, _ptr(dst), _ptr(src), src.numel() * src.element_size()))

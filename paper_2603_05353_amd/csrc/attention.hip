@@ -133,6 +133,18 @@ hipError_t run_generic(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos,
 
 }  // namespace
 
+void attention_plan(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv, size_t scratch_bytes, int64_t out[4]) {
+  const bool generic = (ctx->desc.flags & IFKV_FLAG_FORCE_GENERIC) || !attention_mfma_supported(ctx);
+  if (generic) {  // one launch of the ALU kernel, never cut
+    out[0] = n_rows > 0 ? 1 : 0;
+    out[1] = 1;
+    out[2] = (n_kv + 63) / 64;
+    out[3] = 0;
+    return;
+  }
+  attention_mfma_plan(ctx, n_rows, n_kv, scratch_bytes, out);
+}
+
 size_t attention_scratch_bytes(const ifkv_ctx *ctx) {
   const bool generic = (ctx->desc.flags & IFKV_FLAG_FORCE_GENERIC) || !attention_mfma_supported(ctx);
   return generic ? 0 : attention_mfma_scratch_bytes(ctx);

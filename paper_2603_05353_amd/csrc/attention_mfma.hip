@@ -660,7 +660,7 @@ size_t partial_bytes(const ifkv_ctx *ctx, int64_t n_rows, int parts) {
 struct SplitChoice {
   int parts, part_tiles;
 };
-SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
+SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv, size_t scratch_bytes) {
   const auto &d = ctx->desc;
   const int G = d.n_q_heads / d.n_kv_heads;
   const int rpb = 128 / G;
@@ -691,7 +691,7 @@ SplitChoice choose_split(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv) {
   c.parts = (n_kv_tiles + part_tiles - 1) / part_tiles;
   if (c.parts < 1) c.parts = 1;
   // host-side bounds: the grid's z extent, and the partial results must fit what was allocated
-  if (c.parts > 65535 || (c.parts > 1 && partial_bytes(ctx, n_rows, c.parts) > ctx->scratch_bytes)) {
+  if (c.parts > 65535 || (c.parts > 1 && partial_bytes(ctx, n_rows, c.parts) > scratch_bytes)) {
     c.parts = 1;
     c.part_tiles = n_kv_tiles > 0 ? n_kv_tiles : 1;
   }
@@ -724,7 +724,7 @@ hipError_t launch_attention_range(ifkv_ctx *ctx, const uint16_t *q_sel, const in
   const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
   const int rpb = 128 / G;
   const unsigned n_rb = static_cast<unsigned>((n_rows + rpb - 1) / rpb);
-  const SplitChoice sc = choose_split(ctx, n_rows, n_kv);
+  const SplitChoice sc = choose_split(ctx, n_rows, n_kv, ctx->scratch_bytes);
   SplitPlan sp;
   sp.part_tiles = sc.part_tiles;
   sp.o_part = nullptr;
@@ -754,14 +754,38 @@ hipError_t launch_attention_range(ifkv_ctx *ctx, const uint16_t *q_sel, const in
 
 }  // namespace
 
+namespace {
+int64_t rows_per_launch_of(const ifkv_ctx *ctx) {
+  const int G = ctx->desc.n_q_heads / ctx->desc.n_kv_heads;
+  int64_t max_rb = kMaxRowBlocks;
+  if (ctx->tune.attn_max_row_blocks > 0 && ctx->tune.attn_max_row_blocks < max_rb) max_rb = ctx->tune.attn_max_row_blocks;
+  return max_rb * (128 / G);
+}
+}  // namespace
+
+// What launch_attention_mfma would do for n_rows rows against n_kv keys with a scratch of
+// scratch_bytes: the launches, the largest number of kv parts and the smallest part length among
+// them, and the most bytes of partial results any of them keeps.  Host arithmetic only.
+void attention_mfma_plan(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv, size_t scratch_bytes, int64_t out[4]) {
+  const int64_t rows_per_launch = rows_per_launch_of(ctx);
+  out[0] = out[3] = 0;
+  out[1] = 1;
+  out[2] = (n_kv + TK - 1) / TK;
+  for (int64_t r0 = 0; r0 < n_rows; r0 += rows_per_launch) {
+    const int64_t nr = n_rows - r0 < rows_per_launch ? n_rows - r0 : rows_per_launch;
+    const SplitChoice sc = choose_split(ctx, nr, n_kv, scratch_bytes);
+    ++out[0];
+    if (sc.parts > out[1]) out[1] = sc.parts;
+    if (sc.part_tiles < out[2]) out[2] = sc.part_tiles;
+    if (sc.parts > 1) out[3] = std::max<int64_t>(out[3], static_cast<int64_t>(partial_bytes(ctx, nr, sc.parts)));
+  }
+}
+
 hipError_t launch_attention_mfma(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                                  const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                                  float *lse_out) {
   const auto &d = ctx->desc;
-  const int G = d.n_q_heads / d.n_kv_heads;
-  int64_t max_rb = kMaxRowBlocks;
-  if (ctx->tune.attn_max_row_blocks > 0 && ctx->tune.attn_max_row_blocks < max_rb) max_rb = ctx->tune.attn_max_row_blocks;
-  const int64_t rows_per_launch = max_rb * (128 / G);
+  const int64_t rows_per_launch = rows_per_launch_of(ctx);
   const int64_t row_elems = static_cast<int64_t>(d.n_q_heads) * D;
   for (int64_t r0 = 0; r0 < n_rows; r0 += rows_per_launch) {
     const int64_t nr = n_rows - r0 < rows_per_launch ? n_rows - r0 : rows_per_launch;

@@ -38,13 +38,17 @@ int hip_fail(ifkv_ctx *ctx, hipError_t e, const char *what) {
 // The context's scratch: ONE allocation, on the first stage call that needs scratch, sized for the
 // largest request any stage can make under the layer descriptor (the stages run one after the other
 // on one stream and share it).  No later call allocates, frees or synchronises.
-int ensure_scratch(ifkv_ctx *ctx) {
-  if (ctx->scratch != nullptr) return IFKV_OK;
+size_t scratch_bytes_for(const ifkv_ctx *ctx) {
   size_t bytes = ifkv::score_scratch_bytes(ctx, ctx->desc.max_ctx, ctx->desc.max_prompt);
   bytes = std::max(bytes, ifkv::topk_scratch_bytes(ctx, ctx->desc.max_ctx));
   bytes = std::max(bytes, ifkv::attention_scratch_bytes(ctx));
   bytes = std::max(bytes, ifkv::validate_scratch_bytes(ctx));
-  bytes = std::max<size_t>(bytes, 256);
+  return std::max<size_t>(bytes, 256);
+}
+
+int ensure_scratch(ifkv_ctx *ctx) {
+  if (ctx->scratch != nullptr) return IFKV_OK;
+  const size_t bytes = scratch_bytes_for(ctx);
   void *p = nullptr;
   hipError_t e = hipMalloc(&p, bytes);
   if (e != hipSuccess) {
@@ -563,6 +567,17 @@ int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value) {
     return IFKV_OK;
   }
   return fail(ctx, IFKV_EINVAL, "set_tuning: unknown key '%s'", key);
+}
+
+int ifkv_attention_plan(ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv, int64_t *plan) {
+  if (ctx == nullptr) return IFKV_EINVAL;
+  if (plan == nullptr) return fail(ctx, IFKV_EINVAL, "attention_plan: plan is NULL");
+  if (n_rows < 0 || n_kv < 1 || n_kv > ctx->desc.max_ctx)
+    return fail(ctx, IFKV_EINVAL, "attention_plan: n_rows must be >= 0 and n_kv in [1, max_ctx]");
+  const size_t scratch = ctx->scratch != nullptr ? ctx->scratch_bytes : scratch_bytes_for(ctx);
+  ifkv::attention_plan(ctx, n_rows, n_kv, scratch, plan);
+  plan[4] = static_cast<int64_t>(scratch);
+  return IFKV_OK;
 }
 
 int ifkv_copy_bytes(ifkv_ctx *ctx, void *dst, const void *src, int64_t n_bytes) {

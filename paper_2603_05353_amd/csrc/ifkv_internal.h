@@ -83,6 +83,8 @@ int64_t topk_static_max_ctx();
 
 // Stage 4.
 size_t attention_scratch_bytes(const ifkv_ctx *ctx);
+// {launches, most kv parts, shortest part in tiles, most bytes of partial results} of a stage-4 call
+void attention_plan(const ifkv_ctx *ctx, int64_t n_rows, int64_t n_kv, size_t scratch_bytes, int64_t out[4]);
 hipError_t launch_attention(ifkv_ctx *ctx, const void *q_sel, const int32_t *row_pos, int64_t n_rows,
                             const void *k_cache, const void *v_cache, int64_t n_kv, void *out,
                             float *lse_out);

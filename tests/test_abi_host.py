@@ -228,6 +228,54 @@ def test_set_tuning_validation(lib):
     L.close()
 
 
+def test_attention_plan_stays_within_the_scratch(lib):
+    """Host arithmetic of stage 4's launch plan: whatever the shape and the knobs, the partial results
+    of every launch fit the scratch the context allocates once; cuts that would not fit are not made;
+    launches with a handful of row blocks are cut finer than the usual 8 parts."""
+    shapes = [(32, 8, 32768), (32, 8, 131072), (28, 4, 20480), (8, 8, 4096), (32, 1, 32768), (64, 2, 65536)]
+    knobs = [{}, {"attn_split_parts": 2}, {"attn_split_parts": 65535}, {"attn_part_tiles": 1}, {"attn_part_tiles": 40},
+             {"attn_max_row_blocks": 3}, {"attn_max_row_blocks": 3, "attn_part_tiles": 64},
+             {"attn_max_row_blocks": 40, "attn_split_parts": 3}]
+    for hq, hkv, max_ctx in shapes:
+        rpb = 128 // (hq // hkv)
+        for kn in knobs:
+            L = B.Layer("bf16", hq, hkv, 128, 5e5, max_ctx=max_ctx, max_prompt=128, stream=0)
+            for key, value in kn.items():
+                L.set_tuning(key, value)
+            for n_kv in (1, 64, 65, 2049, max_ctx // 4, max_ctx):
+                for n_rows in (0, 1, rpb, rpb + 1, 8 * rpb, 100 * rpb, int(0.05 * n_kv), int(0.15 * n_kv), int(0.3 * n_kv), n_kv):
+                    p = L.attention_plan(n_rows, n_kv)
+                    tag = (hq, hkv, max_ctx, kn, n_kv, n_rows, p)
+                    assert p["partial_bytes"] <= p["scratch_bytes"], tag
+                    assert 1 <= p["parts"] <= 65535 and p["part_tiles"] >= 1, tag
+                    n_rb = -(-n_rows // rpb)
+                    max_rb = kn.get("attn_max_row_blocks", 65535)
+                    assert p["launches"] == -(-n_rb // max_rb), tag
+                    if p["parts"] == 1:
+                        assert p["partial_bytes"] == 0, tag
+            L.close()
+    # the library's own rule
+    L = B.Layer("bf16", 32, 8, 128, 5e5, max_ctx=131072, max_prompt=128, stream=0)
+    assert L.attention_plan(19661, 131072)["parts"] == 1          # 15 %: more row blocks than slots, never cut
+    assert 2 <= L.attention_plan(1638, 32768)["parts"] <= 8       # 5 % of 32K: cut, at most 8 parts
+    few = L.attention_plan(8, 131072)                             # one row block per kv head
+    assert few["parts"] == 64 and few["part_tiles"] == 32, few
+    assert L.attention_plan(128, 131072)["parts"] == 16           # 32 jobs: 16 parts fill the slots
+    # a forced cut that cannot fit falls back to no cut
+    L.set_tuning("attn_part_tiles", 1)
+    big = L.attention_plan(19661, 131072)
+    assert big["parts"] == 1 and big["partial_bytes"] == 0, big
+    L.close()
+    assert lib.ifkv_attention_plan(None, 1, 1, (C.c_int64 * 5)()) == B.IFKV_EINVAL
+    L = _layer()
+    for bad in [(-1, 10), (1, 0), (1, 10**9)]:
+        with pytest.raises(B.IfkvError) as e:
+            L.attention_plan(*bad)
+        assert e.value.code == B.IFKV_EINVAL
+    assert lib.ifkv_attention_plan(L._ctx, 1, 1, None) == B.IFKV_EINVAL
+    L.close()
+
+
 def test_cache_strides_validation(lib):
     """token_stride / head_stride of the layer descriptor: both or neither, 16-byte multiples, at least
     head_dim, and no overlap of the heads of a row or of the rows of a head."""
