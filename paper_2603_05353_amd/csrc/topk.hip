@@ -63,17 +63,16 @@ __device__ __forceinline__ void transpose32(uint32_t (&a)[32]) {
   }
 }
 
-constexpr int kStageThreads = 256;                 // threads served per staging round
-constexpr int kStageElems = kStageThreads * 32;    // 8192 scores per staging round
-
 // THREADS x WORDS x 32 keys held in registers as bit planes.
 template <int THREADS, int WORDS>
 __global__ __launch_bounds__(THREADS) void topk_resident_kernel(const float *__restrict__ scores, int n, int k,
                                                                 int32_t *__restrict__ idx_out) {
   constexpr int NW = THREADS / 64;
-  constexpr int SUB = THREADS / kStageThreads;
-  constexpr int PER = kStageElems / THREADS;  // scores loaded per thread per staging round
-  __shared__ uint32_t stage[kStageThreads * 33];  // 32 keys per owner thread, padded to 33 words
+  // Thread t owns keys 32 t .. 32 t + 31 of a word.  They are loaded with coalesced 16-byte reads (all
+  // of a thread's eight requests are issued before anything waits: one memory latency for the whole
+  // vector), handed over through LDS (33 words per owner: conflict-free both ways) in one round with
+  // one barrier, and transposed into bit planes.
+  __shared__ uint32_t stage[THREADS * 33];
   __shared__ uint32_t red[2][16][2];
   __shared__ uint32_t wave_tot[16];
 
@@ -85,40 +84,36 @@ __global__ __launch_bounds__(THREADS) void topk_resident_kernel(const float *__r
   uint32_t plane[WORDS][32];
 #pragma unroll
   for (int w = 0; w < WORDS; ++w) {
+    const int base = w * THREADS * 32;
+    float4 f[8];
 #pragma unroll
-    for (int q = 0; q < SUB; ++q) {
-      const int base = (w * THREADS + q * kStageThreads) * 32;
-#pragma unroll
-      for (int i = 0; i < PER / 4; ++i) {
-        const int e = (i * THREADS + tid) * 4;
-        const int gi = base + e;
-        uint32_t k0 = 0, k1 = 0, k2 = 0, k3 = 0;
-        if (vec_ok && gi + 3 < n) {
-          const float4 f = *reinterpret_cast<const float4 *>(scores + gi);
-          k0 = score_key(f.x);
-          k1 = score_key(f.y);
-          k2 = score_key(f.z);
-          k3 = score_key(f.w);
-        } else {
-          if (gi < n) k0 = score_key(scores[gi]);
-          if (gi + 1 < n) k1 = score_key(scores[gi + 1]);
-          if (gi + 2 < n) k2 = score_key(scores[gi + 2]);
-          if (gi + 3 < n) k3 = score_key(scores[gi + 3]);
-        }
-        uint32_t *dst = stage + e + (e >> 5);
-        dst[0] = k0;
-        dst[1] = k1;
-        dst[2] = k2;
-        dst[3] = k3;
+    for (int i = 0; i < 8; ++i) {
+      const int gi = base + (i * THREADS + tid) * 4;
+      f[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (vec_ok && gi + 3 < n) {
+        f[i] = *reinterpret_cast<const float4 *>(scores + gi);
+      } else {
+        if (gi < n) f[i].x = scores[gi];
+        if (gi + 1 < n) f[i].y = scores[gi + 1];
+        if (gi + 2 < n) f[i].z = scores[gi + 2];
+        if (gi + 3 < n) f[i].w = scores[gi + 3];
       }
-      __syncthreads();
-      if ((tid / kStageThreads) == q) {
-        const int t = tid % kStageThreads;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) plane[w][i] = stage[t * 33 + i];
-      }
-      __syncthreads();
     }
+    if (w > 0) __syncthreads();  // the previous word's keys have been taken out of the stage
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = (i * THREADS + tid) * 4;
+      const int gi = base + e;
+      uint32_t *dst = stage + e + (e >> 5);
+      // key 0 pads the tail: every real score maps to a key > 0
+      dst[0] = gi < n ? score_key(f[i].x) : 0u;
+      dst[1] = gi + 1 < n ? score_key(f[i].y) : 0u;
+      dst[2] = gi + 2 < n ? score_key(f[i].z) : 0u;
+      dst[3] = gi + 3 < n ? score_key(f[i].w) : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; ++i) plane[w][i] = stage[tid * 33 + i];
     transpose32(plane[w]);
   }
 
