@@ -11,11 +11,11 @@
 // wavefront streams its own 64-key tiles of K straight from global memory into
 // MFMA operand registers (a key is used by exactly one wavefront, so there is
 // nothing to share through LDS) and walks over the query rows in blocks of 32.
-//   pass A: S^T = K.Q^T, a lane owns one query row -> running (max, sum) per
-//           lane with no cross-lane traffic; merged over lanes, wavefronts and
-//           blocks at the end.
+//   pass A: S^T = K.Q^T, a lane owns one query row -> (reference exponent,
+//           sum) per lane with no cross-lane traffic; merged over lanes,
+//           wavefronts and blocks at the end.
 //   pass B: S = Q.K^T, a lane owns one key -> sum over query rows of
-//           exp2(S*c - b_q) with b_q = log2-domain max + log2 Z, in-lane.
+//           exp2(S*c - b_q) with b_q = log2-domain reference + log2 Z, in-lane.
 #include <algorithm>
 #include <type_traits>
 
