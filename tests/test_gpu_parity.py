@@ -497,6 +497,29 @@ def test_attention_few_rows_against_a_long_context():
     attention_case(spec, rows, q_gain=6.0)
 
 
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_attention_random_shapes_and_knobs(seed):
+    """Seeded draws of head counts (group sizes 1 .. 32), chunkings, row sets (a handful of rows up to
+    several hundred, with and without the first and the last position), logit sharpness and launch knobs."""
+    g = np.random.Generator(np.random.Philox(key=[seed, 31337]))
+    h_kv, grp = int(g.choice([1, 2, 4, 8])), int(g.choice([1, 2, 4, 7, 8, 16, 32]))
+    while h_kv * grp > 64:
+        h_kv //= 2
+    lens = [int(x) for x in g.integers(1, 9000 if seed % 4 == 0 else 900, size=int(g.integers(1, 6)))]
+    n_ctx = sum(lens)
+    k = min(n_ctx, int(g.integers(1, 40))) if seed % 5 == 0 else int(g.integers(1, min(n_ctx, 700) + 1))
+    rows = np.sort(g.choice(n_ctx, size=k, replace=False))
+    if seed % 3 == 0:
+        rows[0] = 0
+    if seed % 7 == 0:
+        rows[-1] = n_ctx - 1
+    tuning = [None, {"attn_part_tiles": int(g.integers(1, 50))}, {"attn_split_parts": int(g.integers(1, 9))},
+              {"attn_max_row_blocks": int(g.integers(1, 6))},
+              {"attn_max_row_blocks": int(g.integers(1, 6)), "attn_part_tiles": int(g.integers(1, 30))}][seed % 5]
+    spec = preset("C2", n_q_heads=h_kv * grp, n_kv_heads=h_kv, chunk_lens=lens, m_prompt=4, seed=20260305 + 900 + seed)
+    attention_case(spec, np.unique(rows), tuning=tuning, q_gain=float(g.choice([1.0, 1.0, 6.0])), n_check=64)
+
+
 # (chunk lengths, selected rows or a count to draw, H_q, H_kv): caches shorter than / equal to / one past a
 # key tile, a single row, every row, the largest and the smallest group size the MFMA path takes
 ATTN_SHAPES = [
@@ -757,7 +780,7 @@ def random_shape_spec(seed):
     return spec, float(g.choice([0.05, 0.15, 0.3, 0.5]))
 
 
-@pytest.mark.parametrize("seed", list(range(1, 13)))
+@pytest.mark.parametrize("seed", list(range(1, 41)))
 def test_composite_layer_random_shapes(seed):
     spec, ratio = random_shape_spec(seed)
     composite_case(spec, ratio, 1e-5 if spec.dtype == "f32" else 1e-4)
