@@ -28,6 +28,13 @@ extern "C" {
  *   "attn_max_row_blocks"   stage 4: row blocks (128 query columns each) per
  *                           launch, 1 .. 65535; more rows take several
  *                           launches; 0 restores the default (65535)
+ *   "attn_exact_sweep"      stage 4 (bf16 MFMA kernel): 1 = every workgroup sweeps
+ *                           its keys with the running maximum right away; 0
+ *                           (default) = first with the logit of the sweep's
+ *                           first key as the fixed reference exponent, and
+ *                           again with the running maximum only if a column's
+ *                           sum shows that some key outweighs that first key
+ *                           by more than 4096 times the number of keys
  *   "fused_repo_score"      ifkv_reposition_score: 1 = take the first scoring
  *                           sweep straight from the chunk caches (one kernel
  *                           re-rotates, stores and scores) where the layer

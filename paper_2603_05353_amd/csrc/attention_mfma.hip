@@ -34,6 +34,7 @@
 // axis: each part leaves its unnormalised O, reference max and sum in scratch and
 // attn_combine_kernel merges them.
 #include <algorithm>
+#include <type_traits>
 
 #include "attention_common.h"
 #include "ifkv_device.h"
@@ -142,9 +143,11 @@ __device__ __forceinline__ void qk_tile(f32x16 (&S)[2], const uint16_t *k_stage,
   }
 }
 
-// Causal mask (only on tiles that reach past the wavefront's smallest position), row max, and
-// the lazy update of the reference max with the rescale of O and l it implies.
+// Causal mask (only on tiles that reach past the wavefront's smallest position) and, in the exact
+// variant, the row max with the lazy update of the reference max and the rescale of O and l it
+// implies.  The fast variant keeps the reference it was given (see the kernel): nothing but the mask.
 // Register r of S[t] is kv row j0 + 32 t + 16 (r / 8) + 8 hf + r % 8.
+template <bool EXACT>
 __device__ __forceinline__ void row_stats(f32x16 (&S)[2], WaveState &w, int j0, int p_q, int p_wmin, int hf,
                                           float scale_log2) {
   if (j0 + TK - 1 > p_wmin) {
@@ -155,6 +158,7 @@ __device__ __forceinline__ void row_stats(f32x16 (&S)[2], WaveState &w, int j0, 
       for (int r = 0; r < 16; ++r)
         if (base + 32 * t + 16 * (r >> 3) + (r & 7) > 0) S[t][r] = -INFINITY;
   }
+  if (!EXACT) return;
   float mx = S[0][0];
 #pragma unroll
   for (int t = 0; t < 2; ++t)
@@ -410,6 +414,7 @@ struct SplitPlan {
   float *o_part;      // [parts][n_rows][H_q][D] unnormalised O
   float2 *ml_part;    // [parts][n_rows][H_q] (reference max in the log2 domain, sum)
   int *block_tiles;   // [row blocks] tile count of each row block (written by part 0)
+  int exact_only;     // 1: skip the fixed-reference sweep
 };
 
 __device__ __forceinline__ void write_partial(const WaveState &w, const Column &c, const SplitPlan &sp, int part,
@@ -561,51 +566,78 @@ __global__ __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 
   constexpr uint32_t kStageBytes = TILE_ELEMS * 2;
 
   WaveState w;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) w.O[dt][r] = 0.f;
-  w.m_run = kNoMax;
-  w.l_run = 0.f;
-
-  // Tiles t0 .. t0+NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
-  // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
-#pragma unroll
-  for (int t = 0; t < NS - 1; ++t)
-    issue_tile_dma<NWAVES>(plan, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
-                           kv_row_elems, t0 + t, n_kv);
-
   const int my_tiles = min(t1, c.p_wmax / TK + 1);
-  // One tile.  `st` is a compile-time constant at every call (the loop below is unrolled over the
-  // ring), so the LDS stage base folds into the immediate offset of every LDS read and the reads
-  // cost no address arithmetic.
-  auto tile_step = [&](int i, int st) {
-    // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
-    // (loads complete in order; the query loads issued before them are therefore complete too)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
-    __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
-    {
-      const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
-      issue_tile_dma<NWAVES>(plan, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
-                             kv_row_elems, i + NS - 1, n_kv);
-    }
-    if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
-      f32x16 S[2];
-      qk_tile(S, k_lds[st], qf, ro);
-      VFrags vf;
-      pv_preload(vf, v_lds[st], ro);
-      row_stats(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
-      PTile P;
-      exp_tile(S, w, P, scale_log2);
-      pv_tile(P, vf, w, v_lds[st], ro);
-    }
-  };
-  for (int i0 = t0; i0 < t1; i0 += NS) {
+  // The sweep over this workgroup's kv tiles, in two variants.  The softmax only needs SOME reference
+  // exponent per query column that keeps exp2(logit - reference) inside the fp32 / bf16 range, not the
+  // column maximum.  The fast variant takes the logit of the first key of the sweep (key t0 * 64: the
+  // reference of both lane halves of a column, which feed one product) and keeps it: no maximum over
+  // the tile, no lane-half exchange, no rescaling of O, ever (2.3 % of the launch at 32K context).
+  // It is accepted when every column's sum stays below 4096 x the keys of the sweep, i.e. when no key
+  // outweighs the first one by more than that: flat and moderately peaked attention.  Otherwise --
+  // sharply peaked columns, where the running maximum makes the dominant probability exactly 1 and
+  // thereby free of rounding error, and sums on their way out of the fp32 range -- the whole
+  // workgroup repeats the sweep in the exact variant, which tracks the running maximum (lazily: O is
+  // rescaled only when a tile exceeds the reference by more than 2^8).
+  auto sweep = [&](auto exact_tag) __attribute__((always_inline)) {
+    constexpr bool kExact = decltype(exact_tag)::value;
 #pragma unroll
-    for (int st = 0; st < NS; ++st)
-      if (i0 + st < t1) tile_step(i0 + st, st);
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) w.O[dt][r] = 0.f;
+    w.m_run = kNoMax;
+    w.l_run = 0.f;
+
+    // Tiles t0 .. t0+NS-2 are requested up front; iteration i requests tile i + NS - 1 (rows past the
+    // end are clamped, the data is never used), so exactly NS-1 tiles are in flight at every wait.
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+      issue_tile_dma<NWAVES>(plan, k_lds_addr + t * kStageBytes, v_lds_addr + t * kStageBytes, k_base, v_base,
+                             kv_row_elems, t0 + t, n_kv);
+
+    // One tile.  `st` is a compile-time constant at every call (the loop below is unrolled over the
+    // ring), so the LDS stage base folds into the immediate offset of every LDS read and the reads
+    // cost no address arithmetic.
+    auto tile_step = [&](int i, int st) __attribute__((always_inline)) {
+      // this wavefront's share of tile i has landed when at most the NS-2 younger tiles are outstanding
+      // (loads complete in order; the query loads issued before them are therefore complete too)
+      __builtin_amdgcn_s_waitcnt(0x0F70 | ((NS - 2) * Dma<NWAVES>::PER_TILE));
+      __syncthreads();  // everyone's share is visible, and everyone is done with tile i-1
+      {
+        const int wr = (st == 0) ? NS - 1 : st - 1;  // the stage tile i-1 occupied
+        issue_tile_dma<NWAVES>(plan, k_lds_addr + wr * kStageBytes, v_lds_addr + wr * kStageBytes, k_base, v_base,
+                               kv_row_elems, i + NS - 1, n_kv);
+      }
+      if (i < my_tiles) {  // otherwise this wavefront's rows end before the tile (it still stages and syncs)
+        f32x16 S[2];
+        qk_tile(S, k_lds[st], qf, ro);
+        VFrags vf;
+        pv_preload(vf, v_lds[st], ro);
+        if (!kExact && i == t0) {
+          // register 0 of the lower lane half is key t0 * 64 (before the mask: a real key's logit even
+          // for a column that does not see it); the upper half takes it from its partner lane
+          w.m_run = __shfl(S[0][0], lane & 31, 64) * scale_log2;
+        }
+        row_stats<kExact>(S, w, i * TK, c.p_q, c.p_wmin, hf, scale_log2);
+        PTile P;
+        exp_tile(S, w, P, scale_log2);
+        pv_tile(P, vf, w, v_lds[st], ro);
+      }
+    };
+    for (int i0 = t0; i0 < t1; i0 += NS) {
+#pragma unroll
+      for (int st = 0; st < NS; ++st)
+        if (i0 + st < t1) tile_step(i0 + st, st);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is reused or released
+  };
+  bool redo = sp.exact_only != 0;
+  if (!redo) {
+    sweep(std::false_type{});
+    const float limit = 4096.f * TK * static_cast<float>(t1 - t0);
+    redo = __syncthreads_or(!(w.l_run <= limit) ? 1 : 0) != 0;  // also true for NaN; uniform over the workgroup
+    // every wavefront has passed that barrier, so nobody still reads the LDS ring
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the look-ahead loads before the LDS is released
+  if (redo) sweep(std::true_type{});
   if (split) {
     write_partial(w, c, sp, part, n_rows, n_q_heads, g, G, hf);
   } else {
@@ -730,6 +762,7 @@ hipError_t launch_attention_range(ifkv_ctx *ctx, const uint16_t *q_sel, const in
   sp.o_part = nullptr;
   sp.ml_part = nullptr;
   sp.block_tiles = nullptr;
+  sp.exact_only = ctx->tune.attn_exact_sweep;
   if (sc.parts > 1) {
     if (ctx->scratch == nullptr || partial_bytes(ctx, n_rows, sc.parts) > ctx->scratch_bytes) return hipErrorInvalidValue;
     const size_t slots = static_cast<size_t>(sc.parts) * static_cast<size_t>(n_rows) * d.n_q_heads;

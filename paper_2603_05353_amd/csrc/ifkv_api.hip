@@ -557,6 +557,7 @@ int ifkv_set_tuning(ifkv_ctx *ctx, const char *key, int64_t value) {
   } knobs[] = {{"attn_split_parts", &ctx->tune.attn_split_parts, 65535},
                {"attn_part_tiles", &ctx->tune.attn_part_tiles, 1 << 24},
                {"attn_max_row_blocks", &ctx->tune.attn_max_row_blocks, 65535},
+               {"attn_exact_sweep", &ctx->tune.attn_exact_sweep, 1},
                {"fused_repo_score", &ctx->tune.fused_repo_score, 1}};
   for (const Knob &k : knobs) {
     if (std::strcmp(key, k.name) != 0) continue;

@@ -14,6 +14,7 @@ struct ifkv_tuning {
   int attn_split_parts = 0;      // stage 4: cut the kv axis into this many equal parts
   int attn_part_tiles = 0;       // stage 4: cut the kv axis into parts of this many tiles (takes precedence)
   int attn_max_row_blocks = 0;   // stage 4: row blocks per launch (can only lower the default)
+  int attn_exact_sweep = 0;      // stage 4: 1 = always sweep with the running maximum (skip the fixed-reference sweep)
   int fused_repo_score = 0;      // stages 1+2 in one call: 1 = take the first scoring sweep from the chunk caches
 };
 

@@ -86,7 +86,7 @@ def assert_attention_close(out, ref, ref_abs, dtype, lse=None, lse_ref=None):
         assert e <= LSE_TOL[dtype], f"log-sum-exp differs by {e}"
 
 
-def needle_case(n_kv, hq, hkv, n_rows, seed):
+def needle_case(n_kv, hq, hkv, n_rows, seed, logit=24.0):
     """Inputs whose outputs are O(1) at any depth: V ~ N(0, 1), and every query column is aligned
     with ONE key of its prefix so strongly that the output is that key's value row to within a few
     per cent.  The target keys cover, per row: position 0, the row's own position, the first and
@@ -110,6 +110,6 @@ def needle_case(n_kv, hq, hkv, n_rows, seed):
             j = fixed[h] if h < len(fixed) else int(g.integers(0, p + 1))
             target[r, h] = j
             kj = K64[j, h // G]
-            Q64[r, h] = (24.0 * d ** 0.5) * kj / (kj @ kj)      # the target's logit is 24 whatever its norm
+            Q64[r, h] = (logit * d ** 0.5) * kj / (kj @ kj)     # the target's logit is `logit` whatever its norm
     K_st, V_st, q_st = (to_storage(x, "bf16") for x in (K64, V64, Q64))
     return rows, target, q_st, K_st, V_st

@@ -218,7 +218,10 @@ def test_set_tuning_validation(lib):
     L.set_tuning("attn_part_tiles", 0)
     L.set_tuning("fused_repo_score", 1)
     L.set_tuning("fused_repo_score", 0)
+    L.set_tuning("attn_exact_sweep", 1)
+    L.set_tuning("attn_exact_sweep", 0)
     for key, value in [("attn_split_parts", 65536), ("attn_split_parts", -1), ("attn_max_row_blocks", 65536), ("fused_repo_score", 2),
+                       ("attn_exact_sweep", 2),
                        ("no_such_knob", 1)]:
         with pytest.raises(B.IfkvError) as e:
             L.set_tuning(key, value)

@@ -596,6 +596,34 @@ def test_attention_needles_at_depth(name, tuning):
     assert np.abs(out - v_all).max() < 0.25
 
 
+@pytest.mark.parametrize("logit", [70.0, 200.0])
+@pytest.mark.parametrize("tuning", [None, {"attn_part_tiles": 7}], ids=["default", "7-tile-parts"])
+def test_attention_needles_far_above_the_first_key(logit, tuning):
+    """The same needles with logits of 70 and 200: exp(logit - logit of the first key of a sweep) is
+    far beyond what the fixed-reference sweep of the MFMA kernel accepts, or overflows fp32 outright, so
+    the workgroups must repeat their sweeps with the running maximum and still give finite, right results."""
+    spec = preset("C2", chunk_lens=[3000], m_prompt=8)
+    rows, target, q_st, K_st, V_st = needle_case(3000, 32, 8, 260, 17, logit=logit)
+    out, lse = run_attention(spec, q_st, rows, K_st, V_st, tuning=tuning)
+    V64 = to_f64(V_st, "bf16")
+    ref, ref_abs, lse_ref = oracle_attention(to_f64(q_st, "bf16"), rows, to_f64(K_st, "bf16"), V64, 128 ** -0.5)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    assert np.abs(ref).max(axis=-1).min() > 1.0
+    assert_attention_close(out, ref, ref_abs, "bf16", lse, lse_ref)
+
+
+@pytest.mark.parametrize("q_gain", [1.0, 2.5, 6.0], ids=["flat", "moderately-peaked", "peaked"])
+def test_attention_fixed_reference_sweep_against_the_exact_one(q_gain):
+    """The MFMA kernel's two sweeps on the same inputs: the library's own choice (the fixed-reference sweep
+    where it is accepted: flat and moderately peaked logits) and the running-maximum sweep forced by the
+    knob, each against the oracle, on whole row blocks and on launches cut along the kv axis."""
+    spec = preset("C2", chunk_lens=[1500, 700, 1000], m_prompt=8)
+    rows = sample_rows(3200, 500, 23)
+    rows[0] = 0
+    for tuning in (None, {"attn_exact_sweep": 1}, {"attn_part_tiles": 9}, {"attn_part_tiles": 9, "attn_exact_sweep": 1}):
+        attention_case(spec, np.unique(rows), tuning=tuning, q_gain=q_gain, n_check=120)
+
+
 def test_attention_needles_gqa7():
     spec = preset("C5", chunk_lens=[3000], m_prompt=8)
     rows, target, q_st, K_st, V_st = needle_case(3000, 28, 4, 300, 5)
