@@ -46,9 +46,9 @@ MFMA_BF16_PEAK = 2.5e15  # flop/s, dense bf16
 # HBM bytes per call of the attention stage (attention kernel, plus the combine pass where the launch
 # is cut) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same counters read
 # for the plain copy kernel: profiles/attn_mfma_kernel_counters_all_configs.md has the commands and
-# the raw readings.  The kernel has not changed since they were taken; None for anything else.
-ATTENTION_TRAFFIC_BYTES = {("C3", 0.15): 8.560e8, ("C3", 0.05): 3.396e8 + 3.9e7, ("C3", 0.3): 8.425e8,
-                           ("C2", 0.15): 8.67e7 + 4.1e7, ("C4", 0.1): 1.624e10, ("C5", 0.15): 1.758e8}
+# the raw readings (taken with the kernels as they are now); None for anything else.
+ATTENTION_TRAFFIC_BYTES = {("C3", 0.15): 8.662e8, ("C3", 0.05): 3.456e8 + 4.0e7, ("C3", 0.3): 8.399e8,
+                           ("C2", 0.15): 8.67e7 + 4.2e7, ("C4", 0.1): 2.003e10, ("C5", 0.15): 1.756e8}
 
 
 def parse():
