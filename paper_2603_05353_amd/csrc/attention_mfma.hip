@@ -14,10 +14,13 @@
 //   P^T = exp2(S^T * c - m)                     (fp32, per-lane statistics: a lane owns one query column)
 //   O^T [128 d x 32 q] += V_tile^T . P^T       (A = V^T from LDS, B = P^T straight from the S^T registers)
 // Computing the transposed products keeps each query column in one lane (two
-// lanes, one per half-wave), so row max / row sum need a single cross-lane
-// exchange per tile, and the S^T accumulator layout is exactly the B-operand
-// layout of the second product once the K rows are fed in a fixed permuted
-// order (sigma below): no LDS round trip for P.
+// lanes, one per half-wave), so a column's statistics need at most one
+// cross-lane exchange per tile, and the S^T accumulator layout is exactly the
+// B-operand layout of the second product once the K rows are fed in a fixed
+// permuted order (sigma below): no LDS round trip for P.  The reference
+// exponent m is, in the first sweep, the logit of the sweep's first key (kept
+// for the whole sweep: no maximum, no exchange, no rescaling); a second sweep
+// with a running maximum follows where the first is not accepted (see the kernel).
 // Staging uses the gfx950 direct global->LDS loads (16 bytes per lane, no registers, no VALU) and
 // keeps NS tiles in an LDS ring.  K rows land in sigma order with their 16-byte chunks XOR-swizzled
 // by the row index, so the A-operand reads (32 rows, one chunk) hit distinct banks.  V lands
